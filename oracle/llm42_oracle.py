@@ -30,10 +30,13 @@ Arithmetic: every floating-point operation is carried out in `acc_dtype`
 bf16 values.  When `round_points` is true the activations that the model keeps
 in bf16 are rounded to bf16 (round-to-nearest-even) at these points and nowhere
 else:
-    residual stream after the embedding lookup (exact) and after each residual add;
     RMSNorm output;  q and k after the rotary embedding;  v;
-    attention output;  SwiGLU output.
-Logits are never rounded.  With `round_points` false the whole forward is the
+    attention output;  SwiGLU output
+(the operands of the matrix products, which the device feeds to bf16 matrix
+units).  The residual stream and the logits are never rounded: the device keeps
+them in fp32.  Rounding the residual stream to bf16 as well was tried and
+rejected: two correct evaluations that differ only in summation order then
+drift apart by more than the logit tolerance after 32 layers.  With `round_points` false the whole forward is the
 textbook real-number definition evaluated in `acc_dtype`; that mode is what the
 pins against an independent library implementation and a brute-force
 implementation use.
@@ -187,13 +190,13 @@ def forward_window(cfg: OracleConfig, weights: dict, kv: OracleKV, seq_len: int,
             p = p / p.sum(dim=-1, keepdim=True)
             attn[:, h, :] = p @ vals[:, g, :]
         attn = _maybe_round(attn.reshape(n, H * hd), round_points)
-        r = _maybe_round(r + attn @ lw["wo"].to(f).T, round_points)
+        r = r + attn @ lw["wo"].to(f).T
 
         y = _maybe_round(rmsnorm(r, lw["ffn_norm"].to(f), cfg.rms_eps), round_points)
         gate = y @ lw["w_gate"].to(f).T
         up = y @ lw["w_up"].to(f).T
         hidden = _maybe_round(silu(gate) * up, round_points)
-        r = _maybe_round(r + hidden @ lw["w_down"].to(f).T, round_points)
+        r = r + hidden @ lw["w_down"].to(f).T
 
     y = _maybe_round(rmsnorm(r, weights["final_norm"].to(f), cfg.rms_eps), round_points)
     return y @ weights["lm_head"].to(f).T

@@ -1,0 +1,269 @@
+// C ABI of the verifier library (declared in include/llm42.h): host-side
+// validation, model construction, workspace carving and the kernel sequence of
+// one verifier pass.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "llm42_dev.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+llm42_status fail(llm42_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return fail(LLM42_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int pad_to(int x, int a) { return (x + a - 1) / a * a; }
+
+llm42_status check_config(const llm42_config& c) {
+  if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.d_ffn < 1 || c.vocab < 1 ||
+      c.max_position < 1)
+    return fail(LLM42_EINVAL, "config: non-positive dimension");
+  if (!(c.rope_theta > 0.f) || !(c.rms_eps >= 0.f)) return fail(LLM42_EINVAL, "config: bad rope_theta / rms_eps");
+  if (c.kv_block_size != LLM42_KV_BLOCK) return fail(LLM42_ESHAPE, "config: kv_block_size must be 16");
+  if (c.head_dim != 64 && c.head_dim != 128) return fail(LLM42_ESHAPE, "config: head_dim must be 64 or 128");
+  if (c.d_model % 128) return fail(LLM42_ESHAPE, "config: d_model must be a multiple of 128");
+  if (c.d_ffn % 16 || c.vocab % 16) return fail(LLM42_ESHAPE, "config: d_ffn and vocab must be multiples of 16");
+  if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 8)
+    return fail(LLM42_ESHAPE, "config: n_q_heads must be 1..8 times n_kv_heads");
+  return LLM42_OK;
+}
+
+// Carve the workspace.  Called with base == nullptr to size it.
+Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context, char* base) {
+  const llm42_config& c = m->cfg;
+  Workspace ws;
+  memset(&ws, 0, sizeof ws);
+  ws.m_rows = num_seqs * window;
+  ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : pad_to(ws.m_rows, 64);
+  ws.r_pad = pad_to(m->group * window, 16);
+  ws.n_super = (max_context + LLM42_SUPERCHUNK - 1) / LLM42_SUPERCHUNK;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off = align_up(off + bytes, 256);
+    return p;
+  };
+  ws.row_pos = (int32_t*)take(sizeof(int32_t) * ws.m_pad);
+  ws.row_seq = (int32_t*)take(sizeof(int32_t) * ws.m_pad);
+  ws.seq_len = (int32_t*)take(sizeof(int32_t) * num_seqs);
+  ws.seq_n = (int32_t*)take(sizeof(int32_t) * num_seqs);
+  ws.dump_slot = (int32_t*)take(sizeof(int32_t) * num_seqs);
+  ws.resid = (float*)take(4ull * ws.m_pad * c.d_model);
+  ws.normed = (uint16_t*)take(2ull * ws.m_pad * c.d_model);
+  ws.q = (uint16_t*)take(2ull * num_seqs * c.n_kv_heads * ws.r_pad * c.head_dim);
+  ws.attn = (uint16_t*)take(2ull * ws.m_pad * m->d_attn);
+  ws.hidden = (uint16_t*)take(2ull * ws.m_pad * m->ffn_k);
+  const size_t part_rows = (size_t)num_seqs * c.n_kv_heads * ws.n_super * ws.r_pad;
+  ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
+  ws.part_ml = (float*)take(8ull * part_rows);
+  ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
+  ws.bytes = off;
+  return ws;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* llm42_last_error(void) { return g_err; }
+
+const char* llm42_schedule_info(void) {
+  return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=1; "
+         "attention: superchunk=1024 keys, step=64 keys, ascending fold; rmsnorm: 4x4 partial sums per row";
+}
+
+llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w, llm42_model** out) {
+  if (!cfg || !w || !out) return fail(LLM42_EINVAL, "model_create: null argument");
+  *out = nullptr;
+  if (llm42_status st = check_config(*cfg)) return st;
+  if (!w->embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+      !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+    return fail(LLM42_EINVAL, "model_create: null weight pointer");
+  const llm42_config& c = *cfg;
+  for (int l = 0; l < c.n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] ||
+        !w->w_up[l] || !w->w_down[l])
+      return fail(LLM42_EINVAL, "model_create: null weight pointer in layer %d", l);
+
+  llm42_model* m = new llm42_model();
+  m->cfg = c;
+  m->group = c.n_q_heads / c.n_kv_heads;
+  m->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  m->d_attn = c.n_q_heads * c.head_dim;
+  m->ffn_k = pad_to(c.d_ffn, 32);
+  m->gu_blocks = m->ffn_k / 8;
+  m->layers = new llm42_model::Layer[c.n_layers];
+
+  // one arena: sizes in bf16 elements, every piece 256-byte aligned
+  const size_t d = c.d_model;
+  const size_t sz_embed = (size_t)c.vocab * d, sz_norm = align_up(d, 128), sz_lm = (size_t)c.vocab * d;
+  const size_t sz_qkv = (size_t)m->n_qkv * d, sz_o = d * m->d_attn, sz_gu = (size_t)m->gu_blocks * 16 * d,
+               sz_down = d * m->ffn_k;
+  const size_t per_layer = 2 * sz_norm + sz_qkv + sz_o + sz_gu + sz_down;
+  const size_t rope_bytes = (size_t)c.max_position * (c.head_dim / 2) * 2 * sizeof(float);
+  const size_t elems = sz_embed + sz_norm + sz_lm + per_layer * c.n_layers;
+  m->arena_bytes = align_up(elems * 2, 256) + rope_bytes;
+  hipError_t e = hipMalloc((void**)&m->arena, m->arena_bytes);
+  if (e != hipSuccess) {
+    delete[] m->layers;
+    delete m;
+    return fail(LLM42_EHIP, "model_create: hipMalloc(%zu): %s", m->arena_bytes, hipGetErrorString(e));
+  }
+  uint16_t* p = m->arena;
+  auto take = [&](size_t n) {
+    uint16_t* r = p;
+    p += n;
+    return r;
+  };
+  m->embed = take(sz_embed);
+  m->final_norm = take(sz_norm);
+  m->lm_head = take(sz_lm);
+  hipStream_t st = nullptr;
+  auto copy = [&](uint16_t* dst, const void* src, size_t n) {
+    return hipMemcpyAsync(dst, src, n * 2, hipMemcpyDeviceToDevice, st);
+  };
+  hipError_t ce = copy(m->embed, w->embed, sz_embed);
+  if (ce == hipSuccess) ce = copy(m->final_norm, w->final_norm, d);
+  launch_pack_plain((const uint16_t*)w->lm_head, m->lm_head, c.vocab, c.d_model, c.d_model, st);
+  for (int l = 0; l < c.n_layers && ce == hipSuccess; ++l) {
+    llm42_model::Layer& ly = m->layers[l];
+    ly.attn_norm = take(sz_norm);
+    ly.ffn_norm = take(sz_norm);
+    ly.wqkv = take(sz_qkv);
+    ly.wo = take(sz_o);
+    ly.wgu = take(sz_gu);
+    ly.wdown = take(sz_down);
+    ce = copy(ly.attn_norm, w->attn_norm[l], d);
+    if (ce == hipSuccess) ce = copy(ly.ffn_norm, w->ffn_norm[l], d);
+    launch_pack_qkv((const uint16_t*)w->wq[l], (const uint16_t*)w->wk[l], (const uint16_t*)w->wv[l], ly.wqkv, c, st);
+    launch_pack_plain((const uint16_t*)w->wo[l], ly.wo, c.d_model, m->d_attn, m->d_attn, st);
+    launch_pack_gate_up((const uint16_t*)w->w_gate[l], (const uint16_t*)w->w_up[l], ly.wgu, c.d_ffn, m->gu_blocks,
+                        c.d_model, st);
+    launch_pack_plain((const uint16_t*)w->w_down[l], ly.wdown, c.d_model, c.d_ffn, m->ffn_k, st);
+  }
+  // rotary table: angle = pos * theta^(-2j/head_dim), evaluated in double, stored as fp32 (cos, sin)
+  m->rope = (float*)((char*)m->arena + align_up(elems * 2, 256));
+  if (ce == hipSuccess) {
+    const int half = c.head_dim / 2;
+    std::vector<float> tab((size_t)c.max_position * half * 2);
+    std::vector<double> inv_freq(half);
+    for (int j = 0; j < half; ++j) inv_freq[j] = std::pow((double)c.rope_theta, -2.0 * j / c.head_dim);
+    for (int pos = 0; pos < c.max_position; ++pos)
+      for (int j = 0; j < half; ++j) {
+        const double a = pos * inv_freq[j];
+        tab[((size_t)pos * half + j) * 2 + 0] = (float)std::cos(a);
+        tab[((size_t)pos * half + j) * 2 + 1] = (float)std::sin(a);
+      }
+    ce = hipMemcpy(m->rope, tab.data(), rope_bytes, hipMemcpyHostToDevice);
+  }
+  if (ce == hipSuccess) ce = hipGetLastError();
+  if (ce == hipSuccess) ce = hipStreamSynchronize(st);
+  if (ce != hipSuccess) {
+    llm42_model_destroy(m);
+    return fail(LLM42_EHIP, "model_create: %s", hipGetErrorString(ce));
+  }
+  *out = m;
+  return LLM42_OK;
+}
+
+void llm42_model_destroy(llm42_model* m) {
+  if (!m) return;
+  if (m->arena) (void)hipFree(m->arena);
+  delete[] m->layers;
+  delete m;
+}
+
+llm42_status llm42_kv_bytes(const llm42_model* m, int64_t num_blocks, size_t* out_bytes) {
+  if (!m || !out_bytes || num_blocks < 0) return fail(LLM42_EINVAL, "kv_bytes: bad argument");
+  *out_bytes = (size_t)m->cfg.n_layers * 2 * (size_t)num_blocks * m->cfg.n_kv_heads * 16 * m->cfg.head_dim * 2;
+  return LLM42_OK;
+}
+
+llm42_status llm42_workspace_bytes(const llm42_model* m, int32_t max_seqs, int32_t window, int32_t max_context,
+                                   size_t* out_bytes) {
+  if (!m || !out_bytes) return fail(LLM42_EINVAL, "workspace_bytes: null argument");
+  if (max_seqs < 1 || window < 1 || window > LLM42_MAX_WINDOW || max_context < 1)
+    return fail(LLM42_EINVAL, "workspace_bytes: max_seqs/window/max_context out of range");
+  if ((int64_t)max_seqs * window > (1 << 20)) return fail(LLM42_EINVAL, "workspace_bytes: more than 2^20 rows");
+  *out_bytes = carve(m, max_seqs, window, max_context, nullptr).bytes;
+  return LLM42_OK;
+}
+
+llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                                 const int32_t* candidates, int32_t window, const int32_t* n_valid, int32_t num_seqs,
+                                 int32_t max_context, int32_t* out_tokens, int32_t* seq_status, float* out_logits,
+                                 const int32_t* dump_seq_ids, int32_t n_dump, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+  if (!m || !kv || !seq_lens || !candidates || !out_tokens || !workspace)
+    return fail(LLM42_EINVAL, "verify_window: null argument");
+  if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
+    return fail(LLM42_EINVAL, "verify_window: bad kv_cache view");
+  if (window < 1 || window > LLM42_MAX_WINDOW) return fail(LLM42_EINVAL, "verify_window: window must be 1..%d", LLM42_MAX_WINDOW);
+  if (num_seqs < 1 || (int64_t)num_seqs * window > (1 << 20)) return fail(LLM42_EINVAL, "verify_window: bad num_seqs");
+  if (n_dump < 0 || (n_dump > 0 && (!out_logits || !dump_seq_ids)))
+    return fail(LLM42_EINVAL, "verify_window: n_dump needs out_logits and dump_seq_ids");
+  if (max_context < 1) return fail(LLM42_EINVAL, "verify_window: max_context < 1");
+  if (max_context > m->cfg.max_position)
+    return fail(LLM42_ECAPACITY, "verify_window: max_context %d exceeds max_position %d", max_context, m->cfg.max_position);
+  if ((int64_t)max_context > (int64_t)kv->max_blocks_per_seq * LLM42_KV_BLOCK)
+    return fail(LLM42_ECAPACITY, "verify_window: max_context %d exceeds block-table capacity %lld", max_context,
+                (long long)kv->max_blocks_per_seq * LLM42_KV_BLOCK);
+  if ((uintptr_t)workspace % 256) return fail(LLM42_EWORKSPACE, "verify_window: workspace not 256-byte aligned");
+  const Workspace ws = carve(m, num_seqs, window, max_context, (char*)workspace);
+  if (ws.bytes > workspace_bytes)
+    return fail(LLM42_EWORKSPACE, "verify_window: workspace %zu < %zu bytes", workspace_bytes, ws.bytes);
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const llm42_config& c = m->cfg;
+  launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context, dump_seq_ids, n_dump,
+                 out_tokens, seq_status, ws, st);
+  launch_embed(m, candidates, ws, st);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const llm42_model::Layer& ly = m->layers[l];
+    launch_rmsnorm(ws.resid, ly.attn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st);
+    launch_gemm_qkv(m, l, kv, window, ws, st);
+    launch_attention(m, l, kv, num_seqs, window, max_context, ws, st);
+    launch_gemm_residual(ly.wo, ws.attn, ws.resid, c.d_model, m->d_attn, ws, st);
+    launch_rmsnorm(ws.resid, ly.ffn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st);
+    launch_gemm_swiglu(m, l, ws, st);
+    launch_gemm_residual(ly.wdown, ws.hidden, ws.resid, c.d_model, m->ffn_k, ws, st);
+  }
+  launch_rmsnorm(ws.resid, m->final_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st);
+  launch_gemm_logits(m, window, n_dump > 0 ? out_logits : nullptr, ws, st);
+  launch_argmax_merge(m, num_seqs, window, out_tokens, ws, st);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LLM42_EHIP, "verify_window: launch failed: %s", hipGetErrorString(e));
+  return LLM42_OK;
+}
+
+llm42_status llm42_commit_rollback(const int32_t* candidates, const int32_t* out_tokens, const int32_t* n_valid,
+                                   int32_t num_seqs, int32_t window, int32_t* seq_lens, int32_t* committed_counts,
+                                   int32_t* committed_tokens, int32_t* rolled_back_counts, void* hip_stream) {
+  if (!candidates || !out_tokens || !seq_lens || !committed_counts || !committed_tokens)
+    return fail(LLM42_EINVAL, "commit_rollback: null argument");
+  if (num_seqs < 1 || window < 1 || window > LLM42_MAX_WINDOW)
+    return fail(LLM42_EINVAL, "commit_rollback: num_seqs/window out of range");
+  launch_commit(candidates, out_tokens, n_valid, num_seqs, window, seq_lens, committed_counts, committed_tokens,
+                rolled_back_counts, (hipStream_t)hip_stream);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LLM42_EHIP, "commit_rollback: launch failed: %s", hipGetErrorString(e));
+  return LLM42_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,156 @@
+// Row-wise kernels of the verifier pass: input validation and row metadata,
+// embedding gather, RMSNorm.
+#include "llm42_dev.h"
+
+namespace {
+
+// One workgroup per sequence.  Validates what only the device can see (lengths,
+// block-table entries, token ids) and writes the row metadata every later kernel
+// uses.  A sequence that fails a check is switched off as a whole: its rows get
+// position -1, no KV slot of it is read or written and its outputs are -1.
+__global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ candidates,
+                               const int32_t* __restrict__ n_valid, const int32_t* __restrict__ block_table,
+                               int max_blocks_per_seq, int64_t num_blocks, int window, int max_context, int vocab,
+                               const int32_t* __restrict__ dump_seq_ids, int n_dump, int32_t* out_tokens,
+                               int32_t* seq_status, int32_t* row_pos, int32_t* row_seq, int32_t* ws_len,
+                               int32_t* ws_n, int32_t* dump_slot) {
+  __shared__ int status;
+  const int s = blockIdx.x;
+  if (threadIdx.x == 0) status = 0;
+  __syncthreads();
+  const int L = seq_lens[s];
+  const int n = n_valid ? n_valid[s] : window;
+  int bad = 0;
+  if (L < 0 || n < 1 || n > window || (int64_t)L + n > max_context) bad = LLM42_SEQ_BAD_LENGTH;
+  if (!bad) {
+    const int blocks = (L + n + LLM42_KV_BLOCK - 1) / LLM42_KV_BLOCK;   // <= max_blocks_per_seq (host checked)
+    for (int b = threadIdx.x; b < blocks; b += blockDim.x) {
+      const int id = block_table[(size_t)s * max_blocks_per_seq + b];
+      if (id < 0 || id >= num_blocks) bad |= LLM42_SEQ_BAD_BLOCK;
+    }
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      const int t = candidates[(size_t)s * window + i];
+      if (t < 0 || t >= vocab) bad |= LLM42_SEQ_BAD_TOKEN;
+    }
+  }
+  if (bad) atomicOr(&status, bad);   // integer OR: order-free
+  __syncthreads();
+  const int st = status;
+  for (int i = threadIdx.x; i < window; i += blockDim.x) {
+    const int row = s * window + i;
+    const bool live = st == 0 && i < n;
+    row_pos[row] = live ? L + i : -1;
+    row_seq[row] = s;
+    out_tokens[row] = -1;              // overwritten by the arg-max merge for live rows
+  }
+  if (threadIdx.x == 0) {
+    ws_len[s] = st == 0 ? L : -1;
+    ws_n[s] = st == 0 ? n : 0;
+    if (seq_status) seq_status[s] = st;
+    int slot = -1;
+    for (int j = 0; j < n_dump; ++j)
+      if (dump_seq_ids[j] == s) slot = j;
+    dump_slot[s] = slot;
+  }
+}
+
+// Rows beyond num_seqs*window that only pad the GEMM grid.
+__global__ void prepare_pad_rows_kernel(int32_t* row_pos, int32_t* row_seq, int from, int to) {
+  const int r = from + blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < to) {
+    row_pos[r] = -1;
+    row_seq[r] = 0;
+  }
+}
+
+// One wave per 16 rows x 32 features of the residual stream: lane
+// (row = lane % 16, g = lane / 16) converts 8 features of its row's embedding to
+// fp32 (exact).  Dead rows get zeros so that everything downstream stays finite.
+__global__ void embed_kernel(const uint16_t* __restrict__ table, const int32_t* __restrict__ candidates,
+                             const int32_t* __restrict__ row_pos, int m_rows, int d, float* __restrict__ resid) {
+  const int col_tiles = d / 32;
+  const size_t tile = (size_t)blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  const int lane = threadIdx.x & 63;
+  const int rb = (int)(tile / col_tiles), cb = (int)(tile % col_tiles);
+  const int row = rb * 16 + (lane & 15);
+  const int feat = cb * 32 + (lane >> 4) * 8;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < m_rows && row_pos[row] >= 0) {
+    const int tok = candidates[row];
+    v = *(const uint4*)(table + (size_t)tok * d + feat);
+  }
+  f32x4 lo = {bf16_bits_to_f32(v.x & 0xFFFFu), bf16_bits_to_f32(v.x >> 16), bf16_bits_to_f32(v.y & 0xFFFFu),
+              bf16_bits_to_f32(v.y >> 16)};
+  f32x4 hi = {bf16_bits_to_f32(v.z & 0xFFFFu), bf16_bits_to_f32(v.z >> 16), bf16_bits_to_f32(v.w & 0xFFFFu),
+              bf16_bits_to_f32(v.w >> 16)};
+  *(f32x4*)(resid + resid_off(row, feat, d)) = lo;
+  *(f32x4*)(resid + resid_off(row, feat + 4, d)) = hi;
+}
+
+// RMSNorm over a 16-row block per workgroup of 4 waves; fp32 residual stream in,
+// bf16 tile layout (the next GEMM's activation operand) out.
+// Reduction schedule per row (a function of d only):
+//   lane (row, g) of wave w accumulates, in feature order, the squares of features
+//   t*32 + g*8 .. +7 for t = w, w+4, w+8, ...;  the 4 g-lanes of a row are then
+//   added by the (lane ^ 16) and (lane ^ 32) butterflies;  the 4 wave sums are
+//   added in wave order.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const uint16_t* __restrict__ gain,
+                                                      uint4* __restrict__ y, int d, float eps) {
+  __shared__ float part[4][16];
+  const int col_tiles = d / 32;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 16 + (lane & 15), g = lane >> 4;
+  uint4* yr = y + (size_t)blockIdx.x * col_tiles * 64 + lane;
+  float ss = 0.f;
+  for (int t = wave; t < col_tiles; t += 4) {
+    const f32x4 a = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
+    const f32x4 b = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[i], a[i], ss);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[i], b[i], ss);
+  }
+  ss += __shfl_xor(ss, 16);
+  ss += __shfl_xor(ss, 32);
+  if (lane < 16) part[wave][lane] = ss;
+  __syncthreads();
+  const int r = lane & 15;
+  const float total = ((part[0][r] + part[1][r]) + part[2][r]) + part[3][r];
+  const float inv = 1.0f / __builtin_sqrtf(total / (float)d + eps);
+  for (int t = wave; t < col_tiles; t += 4) {
+    const f32x4 a = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
+    const f32x4 b = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
+    const uint4 gv = *(const uint4*)(gain + t * 32 + g * 8);
+    uint4 o;
+    o.x = pack2_bf16(a[0] * inv * bf16_bits_to_f32(gv.x & 0xFFFFu), a[1] * inv * bf16_bits_to_f32(gv.x >> 16));
+    o.y = pack2_bf16(a[2] * inv * bf16_bits_to_f32(gv.y & 0xFFFFu), a[3] * inv * bf16_bits_to_f32(gv.y >> 16));
+    o.z = pack2_bf16(b[0] * inv * bf16_bits_to_f32(gv.z & 0xFFFFu), b[1] * inv * bf16_bits_to_f32(gv.z >> 16));
+    o.w = pack2_bf16(b[2] * inv * bf16_bits_to_f32(gv.w & 0xFFFFu), b[3] * inv * bf16_bits_to_f32(gv.w >> 16));
+    yr[(size_t)t * 64] = o;
+  }
+}
+
+}  // namespace
+
+void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                    const int32_t* candidates, const int32_t* n_valid, int num_seqs, int window,
+                    int max_context, const int32_t* dump_seq_ids, int n_dump, int32_t* out_tokens,
+                    int32_t* seq_status, const Workspace& ws, hipStream_t st) {
+  prepare_kernel<<<num_seqs, 64, 0, st>>>(seq_lens, candidates, n_valid, kv->block_table, kv->max_blocks_per_seq,
+                                          kv->num_blocks, window, max_context, m->cfg.vocab, dump_seq_ids, n_dump,
+                                          out_tokens, seq_status, ws.row_pos, ws.row_seq, ws.seq_len, ws.seq_n,
+                                          ws.dump_slot);
+  if (ws.m_pad > ws.m_rows)
+    prepare_pad_rows_kernel<<<(ws.m_pad - ws.m_rows + 63) / 64, 64, 0, st>>>(ws.row_pos, ws.row_seq, ws.m_rows,
+                                                                            ws.m_pad);
+}
+
+void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspace& ws, hipStream_t st) {
+  const int tiles = ws.m_pad / 16 * (m->cfg.d_model / 32);   // a multiple of 4 (d_model % 128 == 0 is checked)
+  embed_kernel<<<tiles / 4, 256, 0, st>>>(m->embed, candidates, ws.row_pos, ws.m_rows, m->cfg.d_model, ws.resid);
+}
+
+void launch_rmsnorm(const float* x, const uint16_t* gain, uint16_t* y, int m_pad, int d, float eps,
+                    hipStream_t st) {
+  rmsnorm_kernel<<<m_pad / 16, 256, 0, st>>>(x, gain, (uint4*)y, d, eps);
+}

@@ -174,11 +174,11 @@ def _brute_force_logits(shape, w, ids, rnd):
                 z = sum(e)
                 for t in range(i + 1):
                     att[i, h * hd:(h + 1) * hd] += e[t] / z * v[t, g * hd:(g + 1) * hd]
-        x = R(x + R(att) @ f(lw["wo"]).T)
+        x = x + R(att) @ f(lw["wo"]).T
         y = R(norm(x, f(lw["ffn_norm"])))
         ga, up = y @ f(lw["w_gate"]).T, y @ f(lw["w_up"]).T
         hdn = R(ga / (1 + np.exp(-ga)) * up)
-        x = R(x + hdn @ f(lw["w_down"]).T)
+        x = x + hdn @ f(lw["w_down"]).T
     return R(norm(x, f(w["final_norm"]))) @ f(w["lm_head"]).T
 
 
