@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the verifier hot path on one MI355X.
+
+A step is one llm42_verify_window + llm42_commit_rollback over one batch of
+synthetic input, with weights, KV cache and inputs already resident in HBM.
+Default workload (N = 1): the 8B-shape single-sequence configuration - 32 layers,
+d 4096, 32 q / 8 kv heads of 128, FFN 14336, vocab 128256, random-init bf16
+weights; one sequence with a 512-token random prompt (KV written by the library's
+own teacher-forced prefill), verification window 32, candidates = the verifier's
+greedy continuation with 2 % random replacements.
+
+Prints one JSON line: verified tokens/s, the roofline of the dominant kernel (the
+gate/up GEMM, HBM bound at 32 rows) timed with HIP events inside the timed steps,
+and the CPU checker timed on the host cores on a bounded sample of the same
+workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+WORKLOADS = {
+    # name: (num_seqs, window, replacement rate, description)
+    "c2": (1, 32, 0.02, "llama-3.1-8B shape random-init, 1 sequence, 512-token prompt, window 32, 2% replaced"),
+}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_candidates(sess, kv, bt, seq_lens, first, window, rate, shape, rng):
+    """Greedy continuation by iterating the verifier to its fixed point (every pass
+    fixes at least one more position), then seeded random replacements."""
+    import numpy as np
+    import torch
+    from paper_2601_17768_amd import workloads as wl
+    n = seq_lens.numel()
+    cand = torch.zeros((n, window), dtype=torch.int32, device=sess.device)
+    cand[:, 0] = first
+    for _ in range(window):
+        out, _, _ = sess.verify(kv, bt, seq_lens, cand)
+        new = cand.clone()
+        new[:, 1:] = out[:, :-1]
+        if torch.equal(new, cand):
+            break
+        cand = new
+    host = wl.replace_candidates(rng, cand.cpu().numpy(), rate, shape.vocab)
+    return torch.as_tensor(host, device=sess.device)
+
+
+def cpu_baseline(shape, weights, window, context, seed):
+    """The CPU checker, as it stands, on one sequence of the workload: one window of
+    `window` rows at the given context.  The KV prefix is seeded N(0,1) noise (only the
+    time matters here).  Returns the JSON object."""
+    import torch
+    from oracle import llm42_oracle as orc
+    from paper_2601_17768_amd import workloads as wl
+    cfg = orc.OracleConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                           shape.d_ffn, shape.vocab, shape.rope_theta, shape.rms_eps)
+    kv = orc.OracleKV(cfg, context + window)
+    g = torch.Generator().manual_seed(seed)
+    kv.k[:, :context] = torch.randn(kv.k[:, :context].shape, generator=g).to(torch.bfloat16).double()
+    kv.v[:, :context] = torch.randn(kv.v[:, :context].shape, generator=g).to(torch.bfloat16).double()
+    tokens = wl.random_tokens(wl.rng_for(seed, 77), window, shape.vocab)
+    t0 = time.time()
+    out, _ = orc.verify_window(cfg, weights, [kv], [context], [tokens])
+    orc.commit_rollback(tokens, out[0], window)
+    dt = time.time() - t0
+    return {"value": window / dt, "unit": "verified tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"1 sequence, one window of {window} rows at context {context}, all {shape.n_layers} layers, "
+                      f"float64 checker, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step kernel by kernel instead of replaying a HIP graph")
+    ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalid as a result)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2601_17768_amd import binding as B
+    from paper_2601_17768_amd import workloads as wl
+    from paper_2601_17768_amd.session import VerifierSession
+
+    num_seqs, window, rate, desc = WORKLOADS[args.workload]
+    shape = wl.LLAMA_8B if args.layers is None else wl.LLAMA_8B.replace(n_layers=args.layers)
+    seed, prompt_len = 42, 512
+    t0 = time.time()
+    weights = wl.make_weights(shape, seed=seed)
+    log(f"weights generated in {time.time() - t0:.1f}s")
+    sess = VerifierSession(shape, weights, max_position=prompt_len + 2 * window, device="cuda:0")
+    log(f"model on device after {time.time() - t0:.1f}s; {B.llm42_schedule_info()}")
+    dev = sess.device
+    prompts = [wl.random_tokens(wl.rng_for(seed, 2, s), prompt_len, shape.vocab) for s in range(num_seqs)]
+    rng = wl.rng_for(seed, 2, 1000)
+    table, num_blocks = wl.make_block_table(rng, [prompt_len + window] * num_seqs, 16, spare_blocks=8)
+    bt = torch.as_tensor(table, device=dev)
+    kv = sess.kv_cache(num_blocks)
+    first = sess.prefill(kv, bt, prompts, window=window)
+    seq_lens0 = torch.full((num_seqs,), prompt_len, dtype=torch.int32, device=dev)
+    cand = build_candidates(sess, kv, bt, seq_lens0, first, window, rate, shape, rng)
+    torch.cuda.synchronize()
+    log(f"prefill + candidates ready after {time.time() - t0:.1f}s")
+
+    max_context = prompt_len + window
+    ws = sess.workspace(num_seqs, window, max_context)
+    out = torch.empty((num_seqs, window), dtype=torch.int32, device=dev)
+    counts = torch.empty(num_seqs, dtype=torch.int32, device=dev)
+    ctoks = torch.empty((num_seqs, window), dtype=torch.int32, device=dev)
+    rolled = torch.empty(num_seqs, dtype=torch.int32, device=dev)
+    lens_work = seq_lens0.clone()
+    stream = torch.cuda.current_stream()
+
+    def step(st=None):
+        lens_work.copy_(seq_lens0)          # the commit advances the lengths: start every step from the same state
+        B.llm42_verify_window(sess.model, kv, num_blocks, bt, lens_work, cand, window, None, max_context, out,
+                              ws, None, None, None, st)
+        B.llm42_commit_rollback(cand, out, None, lens_work, counts, ctoks, rolled, st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    eager_out = out.clone()
+    graph = None
+    if not args.no_graph:
+        # the two hot calls allocate nothing and never synchronise, so a step can be captured once
+        # and replayed as a HIP graph: this removes the host's per-launch cost (about 260 launches)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_out), "graph replay differs from the eager step"
+    run = graph.replay if graph is not None else step
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    # the same steps once more, launched one by one, with HIP events around every launch of the
+    # dominant kernel on the stream it runs on (events cannot be read back from a replayed graph)
+    B.llm42_profile_enable("gate_up", args.steps * shape.n_layers)
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_eager = time.perf_counter() - t2
+    launches = B.llm42_profile_collect(args.steps * shape.n_layers)
+    assert torch.equal(out, eager_out)
+    ms_per_step = dt * 1e3 / args.steps
+    rows = num_seqs * window
+    value = rows * args.steps / dt
+    committed = int(counts.sum())
+
+    # roofline of the gate/up GEMM: algorithmic bytes per launch = packed gate+up weights, read once,
+    # + the activation operand in + the SwiGLU output out
+    gu_ms = float(np.mean([ms for _, ms in launches]))
+    m_pad = 16 if rows <= 16 else 32 if rows <= 32 else (rows + 63) // 64 * 64
+    gu_bytes = 2 * shape.d_model * shape.d_ffn * 2 + m_pad * shape.d_model * 2 + m_pad * shape.d_ffn * 2
+    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gate_up gemm (gemm_stream_kernel, SwiGLU epilogue)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": gu_bytes, "avg_launch_ms": round(gu_ms, 5), "launches_timed": len(launches)}
+    # whole-pass view: weights streamed once per step
+    weight_gbs = shape.gemm_params * 2 / (ms_per_step * 1e-3) / 1e9
+
+    # per-class breakdown of one more (untimed) step, for the log
+    B.llm42_profile_enable(None, 16 * shape.n_layers)
+    step()
+    torch.cuda.synchronize()
+    per_class = {}
+    for name, ms in B.llm42_profile_collect(16 * shape.n_layers):
+        per_class[name] = per_class.get(name, 0.0) + ms
+    log("kernel classes, ms per step: " + ", ".join(f"{k} {v:.3f}" for k, v in per_class.items()) +
+        f"; sum {sum(per_class.values()):.3f}")
+
+    result = {
+        "metric": "verified tokens/s at 8B shape on 1 MI355X", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "num_seqs": num_seqs, "window": window,
+                   "context": prompt_len, "rows_per_step": rows, "n_layers": shape.n_layers,
+                   "committed_tokens_per_step": committed},
+        "roofline": roofline,
+        "pass_weight_stream_GBps": round(weight_gbs, 1),
+        "launch_mode": "hip graph replay" if graph is not None else "eager",
+        "ms_per_step_eager": round(dt_eager * 1e3 / args.steps, 4),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_class.items()},
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU checker on the host cores ...")
+        result["cpu_baseline"] = cpu_baseline(shape, weights, window, prompt_len, seed)
+    sess.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

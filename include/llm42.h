@@ -63,7 +63,7 @@ typedef int32_t llm42_status;
 typedef struct llm42_model llm42_model;  /* opaque; owns repacked device weights + RoPE table */
 
 /* Model dimensions (caller-owned POD).  Supported: head_dim in {64, 128};
- * d_model, n_q_heads*head_dim multiples of 32; d_ffn, vocab multiples of 16;
+ * d_model a multiple of 128; d_ffn, vocab multiples of 16;
  * n_q_heads a multiple of n_kv_heads with ratio <= 8; kv_block_size == 16. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -127,8 +127,8 @@ llm42_status llm42_workspace_bytes(const llm42_model* model, int32_t max_seqs, i
  *
  * Row (s, i), i < n_valid[s], is input token candidates[s][i] at absolute position
  * seq_lens[s] + i.  candidates[s][0] must be a consistent token and the first
- * seq_lens[s] cache entries of s must be consistent (the caller's precondition,
- * Section 4.2: "the first input to the verifier should be consistent").
+ * seq_lens[s] cache entries of s must be consistent (the caller's precondition;
+ * Section 4.2 requires the verifier's first input to come from a consistent state).
  * Effects, all on `hip_stream`:
  *   - cache slots seq_lens[s] .. seq_lens[s]+n_valid[s]-1 of every layer are
  *     overwritten with the verifier's K and V; no other slot is written and no
@@ -178,6 +178,21 @@ llm42_status llm42_commit_rollback(
     int32_t*       committed_tokens,    /* dev [num_seqs][window], out       */
     int32_t*       rolled_back_counts,  /* dev [num_seqs] or NULL, out       */
     void*          hip_stream);
+
+/* Measurement aid (not part of the protocol; process-wide state, not thread safe).
+ * While enabled, every kernel launch of class `kind` (LLM42_K_*, or -1 for all
+ * classes) made by the two hot calls is bracketed by HIP events recorded on the
+ * call's own stream, up to max_launches launches (further ones go untimed).
+ * llm42_profile_collect waits for the recorded events, writes the duration of each
+ * bracketed launch in milliseconds (and its class) in launch order to HOST arrays of
+ * `capacity` entries, stores the count in *n_out, and disables timing again.  Events
+ * are created inside llm42_profile_enable, never inside a hot call. */
+enum {
+  LLM42_K_PREPARE = 0, LLM42_K_EMBED, LLM42_K_RMSNORM, LLM42_K_QKV, LLM42_K_ATTENTION, LLM42_K_O_PROJ,
+  LLM42_K_GATE_UP, LLM42_K_DOWN, LLM42_K_LM_HEAD, LLM42_K_ARGMAX, LLM42_K_COMMIT, LLM42_K_COUNT
+};
+llm42_status llm42_profile_enable(int32_t kind, int32_t max_launches);
+llm42_status llm42_profile_collect(float* ms_out, int32_t* kinds_out, int32_t capacity, int32_t* n_out);
 
 /* Description of the last error on this thread (host string, never NULL). */
 const char* llm42_last_error(void);

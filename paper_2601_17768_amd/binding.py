@@ -23,7 +23,10 @@ LLM42_MAX_WINDOW = 64
 LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0, 1, 2, 4
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
-           "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info")
+           "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
+           "llm42_profile_enable", "llm42_profile_collect")
+KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
+                  "argmax", "commit")
 
 
 class Llm42Error(RuntimeError):
@@ -76,6 +79,11 @@ def load_library(path: Optional[str] = None):
     lib.llm42_verify_window.restype = i32
     lib.llm42_commit_rollback.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.llm42_commit_rollback.restype = i32
+    lib.llm42_profile_enable.argtypes = [i32, i32]
+    lib.llm42_profile_enable.restype = i32
+    lib.llm42_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32,
+                                          ctypes.POINTER(i32)]
+    lib.llm42_profile_collect.restype = i32
     lib.llm42_last_error.argtypes = []
     lib.llm42_last_error.restype = ctypes.c_char_p
     lib.llm42_schedule_info.argtypes = []
@@ -181,3 +189,18 @@ def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_
 
 def llm42_schedule_info() -> str:
     return load_library().llm42_schedule_info().decode()
+
+
+def llm42_profile_enable(kind, max_launches: int) -> None:
+    """kind: a name from KERNEL_CLASSES, or None for every class."""
+    k = -1 if kind is None else KERNEL_CLASSES.index(kind)
+    _check(load_library().llm42_profile_enable(k, max_launches))
+
+
+def llm42_profile_collect(capacity: int):
+    """Returns [(class name, milliseconds)] in launch order and disables timing."""
+    ms = (ctypes.c_float * capacity)()
+    kinds = (ctypes.c_int32 * capacity)()
+    n = ctypes.c_int32()
+    _check(load_library().llm42_profile_collect(ms, kinds, capacity, ctypes.byref(n)))
+    return [(KERNEL_CLASSES[kinds[i]], float(ms[i])) for i in range(n.value)]

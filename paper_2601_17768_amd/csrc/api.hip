@@ -27,6 +27,35 @@ llm42_status fail(llm42_status code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(LLM42_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
   } while (0)
 
+// ---- optional per-launch timing (a measurement aid, off by default) -------------------------
+struct Profiler {
+  int kind = -2;                       // -2 off, -1 every kernel class, >= 0 one class
+  std::vector<hipEvent_t> ev;          // pairs (start, stop)
+  std::vector<int32_t> kinds;
+  size_t used = 0;                     // events recorded so far
+} g_prof;
+
+struct ScopedEvent {
+  hipStream_t st;
+  bool on;
+  ScopedEvent(int kind, hipStream_t s) : st(s), on(false) {
+    if (g_prof.kind == -2 || (g_prof.kind >= 0 && g_prof.kind != kind) || g_prof.used + 2 > g_prof.ev.size()) return;
+    on = true;
+    g_prof.kinds[g_prof.used / 2] = kind;
+    (void)hipEventRecord(g_prof.ev[g_prof.used], st);
+  }
+  ~ScopedEvent() {
+    if (!on) return;
+    (void)hipEventRecord(g_prof.ev[g_prof.used + 1], st);
+    g_prof.used += 2;
+  }
+};
+#define TIMED(kind, call)        \
+  do {                           \
+    ScopedEvent se_(kind, st);   \
+    call;                        \
+  } while (0)
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int pad_to(int x, int a) { return (x + a - 1) / a * a; }
 
@@ -85,7 +114,7 @@ const char* llm42_last_error(void) { return g_err; }
 
 const char* llm42_schedule_info(void) {
   return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=1; "
-         "attention: superchunk=1024 keys, step=64 keys, ascending fold; rmsnorm: 4x4 partial sums per row";
+         "attention: superchunk=1024 keys, step=64 keys, ascending fold; rmsnorm: 16x4 partial sums per row";
 }
 
 llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w, llm42_model** out) {
@@ -231,22 +260,22 @@ llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv,
 
   hipStream_t st = (hipStream_t)hip_stream;
   const llm42_config& c = m->cfg;
-  launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context, dump_seq_ids, n_dump,
-                 out_tokens, seq_status, ws, st);
-  launch_embed(m, candidates, ws, st);
+  TIMED(LLM42_K_PREPARE, launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context,
+                                        dump_seq_ids, n_dump, out_tokens, seq_status, ws, st));
+  TIMED(LLM42_K_EMBED, launch_embed(m, candidates, ws, st));
   for (int l = 0; l < c.n_layers; ++l) {
     const llm42_model::Layer& ly = m->layers[l];
-    launch_rmsnorm(ws.resid, ly.attn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st);
-    launch_gemm_qkv(m, l, kv, window, ws, st);
-    launch_attention(m, l, kv, num_seqs, window, max_context, ws, st);
-    launch_gemm_residual(ly.wo, ws.attn, ws.resid, c.d_model, m->d_attn, ws, st);
-    launch_rmsnorm(ws.resid, ly.ffn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st);
-    launch_gemm_swiglu(m, l, ws, st);
-    launch_gemm_residual(ly.wdown, ws.hidden, ws.resid, c.d_model, m->ffn_k, ws, st);
+    TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, ly.attn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
+    TIMED(LLM42_K_QKV, launch_gemm_qkv(m, l, kv, window, ws, st));
+    TIMED(LLM42_K_ATTENTION, launch_attention(m, l, kv, num_seqs, window, max_context, ws, st));
+    TIMED(LLM42_K_O_PROJ, launch_gemm_residual(ly.wo, ws.attn, ws.resid, c.d_model, m->d_attn, ws, st));
+    TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, ly.ffn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
+    TIMED(LLM42_K_GATE_UP, launch_gemm_swiglu(m, l, ws, st));
+    TIMED(LLM42_K_DOWN, launch_gemm_residual(ly.wdown, ws.hidden, ws.resid, c.d_model, m->ffn_k, ws, st));
   }
-  launch_rmsnorm(ws.resid, m->final_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st);
-  launch_gemm_logits(m, window, n_dump > 0 ? out_logits : nullptr, ws, st);
-  launch_argmax_merge(m, num_seqs, window, out_tokens, ws, st);
+  TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, m->final_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
+  TIMED(LLM42_K_LM_HEAD, launch_gemm_logits(m, window, n_dump > 0 ? out_logits : nullptr, ws, st));
+  TIMED(LLM42_K_ARGMAX, launch_argmax_merge(m, num_seqs, window, out_tokens, ws, st));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(LLM42_EHIP, "verify_window: launch failed: %s", hipGetErrorString(e));
   return LLM42_OK;
@@ -259,10 +288,42 @@ llm42_status llm42_commit_rollback(const int32_t* candidates, const int32_t* out
     return fail(LLM42_EINVAL, "commit_rollback: null argument");
   if (num_seqs < 1 || window < 1 || window > LLM42_MAX_WINDOW)
     return fail(LLM42_EINVAL, "commit_rollback: num_seqs/window out of range");
-  launch_commit(candidates, out_tokens, n_valid, num_seqs, window, seq_lens, committed_counts, committed_tokens,
-                rolled_back_counts, (hipStream_t)hip_stream);
+  hipStream_t st = (hipStream_t)hip_stream;
+  TIMED(LLM42_K_COMMIT, launch_commit(candidates, out_tokens, n_valid, num_seqs, window, seq_lens, committed_counts,
+                                      committed_tokens, rolled_back_counts, st));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(LLM42_EHIP, "commit_rollback: launch failed: %s", hipGetErrorString(e));
+  return LLM42_OK;
+}
+
+llm42_status llm42_profile_enable(int32_t kind, int32_t max_launches) {
+  if (kind < -1 || kind >= LLM42_K_COUNT || max_launches < 1 || max_launches > (1 << 20))
+    return fail(LLM42_EINVAL, "profile_enable: bad kind or max_launches");
+  while (g_prof.ev.size() < 2 * (size_t)max_launches) {
+    hipEvent_t e;
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) return fail(LLM42_EHIP, "profile_enable: hipEventCreate: %s", hipGetErrorString(err));
+    g_prof.ev.push_back(e);
+  }
+  g_prof.kinds.assign(g_prof.ev.size() / 2, -1);
+  g_prof.used = 0;
+  g_prof.kind = kind;
+  return LLM42_OK;
+}
+
+llm42_status llm42_profile_collect(float* ms_out, int32_t* kinds_out, int32_t capacity, int32_t* n_out) {
+  if (!ms_out || !n_out || capacity < 0) return fail(LLM42_EINVAL, "profile_collect: bad argument");
+  const size_t n = g_prof.used / 2;
+  g_prof.kind = -2;
+  *n_out = 0;
+  for (size_t i = 0; i < n && (int32_t)i < capacity; ++i) {
+    hipError_t err = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms_out[i], g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+    if (err != hipSuccess) return fail(LLM42_EHIP, "profile_collect: %s", hipGetErrorString(err));
+    if (kinds_out) kinds_out[i] = g_prof.kinds[i];
+    *n_out = (int32_t)i + 1;
+  }
+  g_prof.used = 0;
   return LLM42_OK;
 }
 

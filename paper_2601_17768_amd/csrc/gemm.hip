@@ -151,19 +151,74 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const bf16x8* __restri
   for (int b = 0; b < MB; ++b) epi(nb, lane, (mb0 + b) * 16 + (lane & 15), acc[b]);
 }
 
+// Small-batch kernel (at most 64 tokens): HBM-bound weight streaming.
+// One workgroup of 4 waves per block of 16 features.  All 4 waves fetch the
+// block's weight tiles, CH k-tiles per round (CH KiB in flight per workgroup,
+// each wave fetching every 4th tile), and park them in LDS; waves 0 .. MB-1 then
+// each advance one 16-token block's accumulator through the round's tiles in
+// ascending k order, with their own activation tiles prefetched in registers.
+// The next round's weight loads are issued before the current round is consumed.
+// Only the fetch is spread over the waves: the accumulation order per output
+// element is the one stated at the top of this file.
+template <int MB, class Epi>
+__global__ __launch_bounds__(256) void gemm_coop_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
+                                                        int k_tiles, Epi epi) {
+  constexpr int CH = 32;
+  __shared__ bf16x8 wlds[CH * 64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nb = blockIdx.x;
+  const bf16x8* wp = w + (size_t)nb * k_tiles * 64 + lane;
+  const bf16x8* xp = x + (size_t)wave * k_tiles * 64 + lane;   // consumer `wave` owns token block `wave`
+  const bool consumer = wave < MB;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  bf16x8 wr[CH / 4], xr[CH];
+#pragma unroll
+  for (int i = 0; i < CH / 4; ++i)
+    if (i * 4 + wave < k_tiles) wr[i] = __builtin_nontemporal_load(wp + (size_t)(i * 4 + wave) * 64);
+  if (consumer) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+      if (j < k_tiles) xr[j] = xp[(size_t)j * 64];
+  }
+  for (int c0 = 0; c0 < k_tiles; c0 += CH) {
+    const int nt = min(CH, k_tiles - c0);
+#pragma unroll
+    for (int i = 0; i < CH / 4; ++i)
+      if (i * 4 + wave < nt) wlds[(i * 4 + wave) * 64 + lane] = wr[i];
+    __syncthreads();
+    const int n1 = c0 + CH;   // first tile of the next round
+#pragma unroll
+    for (int i = 0; i < CH / 4; ++i)
+      if (n1 + i * 4 + wave < k_tiles) wr[i] = __builtin_nontemporal_load(wp + (size_t)(n1 + i * 4 + wave) * 64);
+    if (consumer) {
+#pragma unroll
+      for (int j = 0; j < CH; ++j)
+        if (j < nt) acc = mfma16(wlds[j * 64 + lane], xr[j], acc);
+#pragma unroll
+      for (int j = 0; j < CH; ++j)
+        if (n1 + j < k_tiles) xr[j] = xp[(size_t)(n1 + j) * 64];
+    }
+    __syncthreads();
+  }
+  if (consumer) epi(nb, lane, wave * 16 + (lane & 15), acc);
+}
+
 template <class Epi>
 void launch_stream(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padded, int m_pad, const Epi& epi,
                    hipStream_t st) {
   const int k_tiles = k_padded / 32;
-  const unsigned gx = (unsigned)((n_blocks + 3) / 4);
   const bf16x8* wp = (const bf16x8*)w;
   const bf16x8* xp = (const bf16x8*)x;
-  if (m_pad % 64 == 0)
+  if (m_pad == 16) {
+    gemm_coop_kernel<1, Epi><<<n_blocks, 256, 0, st>>>(wp, xp, k_tiles, epi);
+  } else if (m_pad == 32) {
+    gemm_coop_kernel<2, Epi><<<n_blocks, 256, 0, st>>>(wp, xp, k_tiles, epi);
+  } else if (m_pad == 64) {
+    gemm_coop_kernel<4, Epi><<<n_blocks, 256, 0, st>>>(wp, xp, k_tiles, epi);
+  } else {   // m_pad is a multiple of 64
+    const unsigned gx = (unsigned)((n_blocks + 3) / 4);
     gemm_stream_kernel<4, Epi><<<dim3(gx, m_pad / 64), 256, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
-  else if (m_pad % 32 == 0)
-    gemm_stream_kernel<2, Epi><<<dim3(gx, m_pad / 32), 256, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
-  else
-    gemm_stream_kernel<1, Epi><<<dim3(gx, m_pad / 16), 256, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+  }
 }
 
 }  // namespace

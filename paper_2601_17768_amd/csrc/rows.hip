@@ -87,46 +87,76 @@ __global__ void embed_kernel(const uint16_t* __restrict__ table, const int32_t* 
   *(f32x4*)(resid + resid_off(row, feat + 4, d)) = hi;
 }
 
-// RMSNorm over a 16-row block per workgroup of 4 waves; fp32 residual stream in,
-// bf16 tile layout (the next GEMM's activation operand) out.
+// RMSNorm over a 16-row block per workgroup of NORM_WAVES waves; fp32 residual
+// stream in, bf16 tile layout (the next GEMM's activation operand) out.
 // Reduction schedule per row (a function of d only):
 //   lane (row, g) of wave w accumulates, in feature order, the squares of features
-//   t*32 + g*8 .. +7 for t = w, w+4, w+8, ...;  the 4 g-lanes of a row are then
-//   added by the (lane ^ 16) and (lane ^ 32) butterflies;  the 4 wave sums are
+//   t*32 + g*8 .. +7 for t = w, w+16, w+32, ...;  the 4 g-lanes of a row are then
+//   added by the (lane ^ 16) and (lane ^ 32) butterflies;  the 16 wave sums are
 //   added in wave order.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const uint16_t* __restrict__ gain,
+constexpr int NORM_WAVES = 16;
+__global__ __launch_bounds__(NORM_WAVES * 64) void rmsnorm_kernel(const float* __restrict__ x, const uint16_t* __restrict__ gain,
                                                       uint4* __restrict__ y, int d, float eps) {
-  __shared__ float part[4][16];
+  __shared__ float part[NORM_WAVES][16];
   const int col_tiles = d / 32;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 16 + (lane & 15), g = lane >> 4;
   uint4* yr = y + (size_t)blockIdx.x * col_tiles * 64 + lane;
   float ss = 0.f;
-  for (int t = wave; t < col_tiles; t += 4) {
-    const f32x4 a = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
-    const f32x4 b = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
+  constexpr int U = 8;   // tiles in flight per wave
+  for (int t0 = wave; t0 < col_tiles; t0 += NORM_WAVES * U) {
+    f32x4 a[U], b[U];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[i], a[i], ss);
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * NORM_WAVES;
+      if (t < col_tiles) {
+        a[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
+        b[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
+      }
+    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[i], b[i], ss);
+    for (int u = 0; u < U; ++u) {
+      if (t0 + u * NORM_WAVES < col_tiles) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[u][i], a[u][i], ss);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[u][i], b[u][i], ss);
+      }
+    }
   }
   ss += __shfl_xor(ss, 16);
   ss += __shfl_xor(ss, 32);
   if (lane < 16) part[wave][lane] = ss;
   __syncthreads();
   const int r = lane & 15;
-  const float total = ((part[0][r] + part[1][r]) + part[2][r]) + part[3][r];
+  float total = part[0][r];
+#pragma unroll
+  for (int w = 1; w < NORM_WAVES; ++w) total += part[w][r];
   const float inv = 1.0f / __builtin_sqrtf(total / (float)d + eps);
-  for (int t = wave; t < col_tiles; t += 4) {
-    const f32x4 a = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
-    const f32x4 b = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
-    const uint4 gv = *(const uint4*)(gain + t * 32 + g * 8);
-    uint4 o;
-    o.x = pack2_bf16(a[0] * inv * bf16_bits_to_f32(gv.x & 0xFFFFu), a[1] * inv * bf16_bits_to_f32(gv.x >> 16));
-    o.y = pack2_bf16(a[2] * inv * bf16_bits_to_f32(gv.y & 0xFFFFu), a[3] * inv * bf16_bits_to_f32(gv.y >> 16));
-    o.z = pack2_bf16(b[0] * inv * bf16_bits_to_f32(gv.z & 0xFFFFu), b[1] * inv * bf16_bits_to_f32(gv.z >> 16));
-    o.w = pack2_bf16(b[2] * inv * bf16_bits_to_f32(gv.w & 0xFFFFu), b[3] * inv * bf16_bits_to_f32(gv.w >> 16));
-    yr[(size_t)t * 64] = o;
+  for (int t0 = wave; t0 < col_tiles; t0 += NORM_WAVES * U) {
+    f32x4 a[U], b[U];
+    uint4 gv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * NORM_WAVES;
+      if (t < col_tiles) {
+        a[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
+        b[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
+        gv[u] = *(const uint4*)(gain + t * 32 + g * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * NORM_WAVES;
+      if (t < col_tiles) {
+        uint4 o;
+        o.x = pack2_bf16(a[u][0] * inv * bf16_bits_to_f32(gv[u].x & 0xFFFFu), a[u][1] * inv * bf16_bits_to_f32(gv[u].x >> 16));
+        o.y = pack2_bf16(a[u][2] * inv * bf16_bits_to_f32(gv[u].y & 0xFFFFu), a[u][3] * inv * bf16_bits_to_f32(gv[u].y >> 16));
+        o.z = pack2_bf16(b[u][0] * inv * bf16_bits_to_f32(gv[u].z & 0xFFFFu), b[u][1] * inv * bf16_bits_to_f32(gv[u].z >> 16));
+        o.w = pack2_bf16(b[u][2] * inv * bf16_bits_to_f32(gv[u].w & 0xFFFFu), b[u][3] * inv * bf16_bits_to_f32(gv[u].w >> 16));
+        yr[(size_t)t * 64] = o;
+      }
+    }
   }
 }
 
@@ -152,5 +182,5 @@ void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspa
 
 void launch_rmsnorm(const float* x, const uint16_t* gain, uint16_t* y, int m_pad, int d, float eps,
                     hipStream_t st) {
-  rmsnorm_kernel<<<m_pad / 16, 256, 0, st>>>(x, gain, (uint4*)y, d, eps);
+  rmsnorm_kernel<<<m_pad / 16, NORM_WAVES * 64, 0, st>>>(x, gain, (uint4*)y, d, eps);
 }
