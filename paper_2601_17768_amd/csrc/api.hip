@@ -81,7 +81,10 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.m_rows = num_seqs * window;
   ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : pad_to(ws.m_rows, 64);
   ws.r_pad = pad_to(m->group * window, 16);
-  ws.n_super = (max_context + LLM42_SUPERCHUNK - 1) / LLM42_SUPERCHUNK;
+  // attention work split: per chunk while the grid would otherwise be small, per super beyond that
+  const int col_blocks = ws.r_pad / 16, cb_groups = (col_blocks + (col_blocks >= 8 ? 8 : 4) - 1) / (col_blocks >= 8 ? 8 : 4);
+  ws.attn_super = (long long)num_seqs * c.n_kv_heads * cb_groups >= 512;
+  ws.attn_units = attention_units(ws.attn_super, max_context);
   size_t off = 0;
   auto take = [&](size_t bytes) {
     char* p = base ? base + off : nullptr;
@@ -98,10 +101,11 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.q = (uint16_t*)take(2ull * num_seqs * c.n_kv_heads * ws.r_pad * c.head_dim);
   ws.attn = (uint16_t*)take(2ull * ws.m_pad * m->d_attn);
   ws.hidden = (uint16_t*)take(2ull * ws.m_pad * m->ffn_k);
-  const size_t part_rows = (size_t)num_seqs * c.n_kv_heads * ws.n_super * ws.r_pad;
+  const size_t part_rows = (size_t)num_seqs * c.n_kv_heads * ws.attn_units * ws.r_pad;
   ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
   ws.part_ml = (float*)take(8ull * part_rows);
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
+  ws.split_part = (float*)take(ws.m_pad > 64 ? 4ull * ws.m_pad * c.d_model : 0);
   ws.bytes = off;
   return ws;
 }
@@ -113,8 +117,8 @@ extern "C" {
 const char* llm42_last_error(void) { return g_err; }
 
 const char* llm42_schedule_info(void) {
-  return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=1; "
-         "attention: superchunk=1024 keys, step=64 keys, ascending fold; rmsnorm: 16x4 partial sums per row";
+  return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=2 (halves, p0+p1) for the two residual projections, 1 elsewhere; "
+         "attention: step=64 keys, chunk=256, super=2048, left folds; rmsnorm: 16x4 partial sums per row";
 }
 
 llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w, llm42_model** out) {

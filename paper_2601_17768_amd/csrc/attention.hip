@@ -3,29 +3,34 @@
 //
 // Reduction schedule of one query row at absolute position p (it depends on p
 // and on nothing else - not on the window, the row's index in it, the batch, or
-// the context lengths of other sequences):
-//   * keys are cut at absolute positions into super-chunks of LLM42_SUPERCHUNK;
-//     super-chunk c holds keys [c*SC, min((c+1)*SC, p+1));
-//   * inside a super-chunk the state (m, l, acc) starts at (-inf, 0, 0) and is
-//     advanced by online-softmax steps over LLM42_KEYSTEP keys in ascending
-//     order (also cut at absolute positions); a step computes its scores with 4
-//     MFMA k-steps per 16-key block, reduces max and sum over its 64 keys in a
-//     fixed tree, rescales, and adds P V with two MFMA k-steps of 32 keys;
-//   * the super-chunk partials are folded in ascending order (merge kernel).
-// Keys beyond p contribute exact zeros (masked before the exponential) and a
-// step in which every key of a row is masked leaves that row's state bit for bit
-// unchanged, so rows of different positions can share a wave.
+// the context lengths of other sequences).  Keys are cut at absolute positions:
+//   step   = 64 keys   [64 j, 64 j + 64)
+//   chunk  = 256 keys  = 4 steps
+//   super  = 2048 keys = 8 chunks
+// * A chunk partial (m, l, acc) starts at (-inf, 0, 0) and is advanced by one
+//   online-softmax step per 64 keys in ascending order; a step computes its
+//   scores with head_dim/32 MFMA k-steps per 16-key block, takes max and sum
+//   over its 64 keys in a fixed tree, rescales, and adds P V with two MFMA
+//   k-steps of 32 keys.
+// * The chunk partials of a super are folded left to right (fold() below), giving
+//   the super partial; the super partials are folded left to right, giving the row.
+// Keys beyond p contribute exact zeros (masked before the exponential); a step or
+// a chunk in which every key of a row is masked leaves that row's state bit for
+// bit unchanged, so rows of different positions can share a workgroup.
 //
-// Work distribution (free to change, does not touch the bits): one wave per
-// (super-chunk, block of 16 query rows, sequence x kv head); the query rows of a
-// kv head are ordered r = q_head_in_group * window + i.  K, V and Q operands are
-// read straight from HBM/L2 in MFMA operand order (see the KV tile layouts in
-// llm42.h), so no LDS transpose is needed.
+// Work distribution (free to change, does not touch the bits): a workgroup of 4
+// waves owns one unit of keys - a chunk (few sequences: more parallelism, chunk
+// partials are written and merge_kernel does all folds) or a whole super (many
+// sequences: chunk partials are folded in registers, 8 times fewer partials go
+// through HBM) - for up to 8 blocks of 16 query rows of one (sequence, kv head);
+// query rows are ordered r = q_head_in_group * window + i.  K and V tiles are
+// fetched once per workgroup, 128 keys at a time, double buffered through LDS in
+// MFMA operand order (see the KV tile layouts in llm42.h), so no transpose is needed.
 #include "llm42_dev.h"
 
 namespace {
 
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+constexpr int STEP = 64, CHUNK = 256, SUPER_KEYS = 2048, STAGE = 128;
 
 union Frag {
   bf16x8 v;
@@ -33,152 +38,262 @@ union Frag {
   uint2 h[2];
 };
 
-template <int HD>
+// state <- state (+) part, the only way two partials are ever combined.
+template <int NV>
+__device__ inline void fold(float& M, float& L, f32x4 (&A)[NV], float m2, float l2, const f32x4 (&a2)[NV]) {
+  const float mn = fmaxf(M, m2);
+  const float mu = mn == -INFINITY ? 0.f : mn;
+  const float a = __builtin_amdgcn_exp2f(M - mu), b = __builtin_amdgcn_exp2f(m2 - mu);
+  L = L * a + l2 * b;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) A[i] = A[i] * a + a2[i] * b;
+  M = mn;
+}
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+// Copy one KV tile (TL KiB) from global memory to LDS without passing through registers.
+// `src` already includes this lane's 16-byte offset; `dst` is the wave-uniform tile base.
+template <int TL>
+__device__ __forceinline__ void tile_to_lds(uint4* dst, const uint4* src) {
+#pragma unroll
+  for (int i = 0; i < TL; ++i)
+    __builtin_amdgcn_global_load_lds((const void*)(src + i * 64), (lds_ptr)(dst + i * 64), 16, 0, 0);
+}
+
+template <int HD, int CB, bool SUPER>
 __global__ __launch_bounds__(256) void attention_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_plane, const uint16_t* __restrict__ v_plane,
+    const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
-    int n_kv_heads, int group, int window, int r_pad, int max_blocks_per_seq, int n_super, float scale_log2,
+    int n_kv_heads, int group, int window, int r_pad, int max_blocks_per_seq, int n_units, float scale_log2,
     float* __restrict__ part_acc, float* __restrict__ part_ml) {
-  constexpr int DK = HD / 32;   // MFMA k-steps over the head dimension (scores)
-  constexpr int DB = HD / 16;   // 16-feature blocks of the output
+  constexpr int DK = HD / 32;        // MFMA k-steps over the head dimension (scores)
+  constexpr int DB = HD / 16;        // 16-feature blocks of the output
+  constexpr int TV4 = HD * 2;        // uint4 per KV tile (16 tokens x HD bf16)
+  constexpr int TL = TV4 / 64;       // uint4 per lane per tile
+  constexpr int UNIT = SUPER ? SUPER_KEYS : CHUNK;
+  __shared__ uint4 lds_k[2][8 * TV4];
+  __shared__ uint4 lds_v[2][8 * TV4];
+  __shared__ int wg_max[4];
+
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int c = blockIdx.x;
-  const int cb = blockIdx.y * 4 + wave;
-  const int s = blockIdx.z / n_kv_heads, kvh = blockIdx.z % n_kv_heads;
-  if (cb * 16 >= r_pad) return;
-  const int L = seq_len[s], n = seq_n[s];
-  if (L < 0) return;
   const int col = lane & 15, g = lane >> 4;
-  const int r = cb * 16 + col;
-  const int i = r % window;
-  const bool live = r < group * window && i < n;
-  const int qpos = live ? L + i : -1;
-  const int k_begin = c * LLM42_SUPERCHUNK;
-  // last position any row of this wave may look at
-  int wave_max = qpos;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) wave_max = max(wave_max, __shfl_xor(wave_max, off));
-  if (wave_max < k_begin) return;
-  const int k_end = min(wave_max + 1, k_begin + LLM42_SUPERCHUNK);   // exclusive
-  const int total = L + n;                                          // first position that holds garbage
-
-  const uint16_t* qbase = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)cb * DK * 512;
-  Frag qf[DK];
-#pragma unroll
-  for (int d = 0; d < DK; ++d) qf[d].u = *(const uint4*)(qbase + d * 512 + lane * 8);
-
-  float m = -INFINITY, l = 0.f;
-  f32x4 acc[DB];
-#pragma unroll
-  for (int d = 0; d < DB; ++d) acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const int unit = blockIdx.x;
+  const int s = blockIdx.z / n_kv_heads, kvh = blockIdx.z % n_kv_heads;
+  const int L = seq_len[s], n = seq_n[s];
+  if (L < 0) return;                                         // whole workgroup
+  const int k_lo = unit * UNIT;
   const int32_t* bt = block_table + (size_t)s * max_blocks_per_seq;
 
-  for (int k0 = k_begin; k0 < k_end; k0 += LLM42_KEYSTEP) {
-    // ---- scores of 4 blocks of 16 keys: S^T[key][query] -------------------------------
-    f32x4 sc[4];
-    int blk[4];
+  int qpos[CB], row[CB];
+  int wmax = -1;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int kb0 = k0 + b * 16;
-      sc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      blk[b] = -1;
-      if (kb0 < k_end) {   // wave-uniform
-        blk[b] = bt[kb0 >> 4];
-        const uint16_t* kt = k_plane + ((size_t)blk[b] * n_kv_heads + kvh) * 16 * HD;
+  for (int cb = 0; cb < CB; ++cb) {
+    row[cb] = ((blockIdx.y * 4 + wave) * CB + cb) * 16 + col;
+    const int i = row[cb] % window;
+    qpos[cb] = (row[cb] < group * window && i < n) ? L + i : -1;
+    wmax = max(wmax, qpos[cb]);
+  }
 #pragma unroll
-        for (int d = 0; d < DK; ++d) {
-          Frag kf;
-          kf.u = *(const uint4*)(kt + d * 512 + lane * 8);
-          sc[b] = mfma16(kf.v, qf[d].v, sc[b]);
-        }
-      }
-    }
-    // ---- mask, running max -------------------------------------------------------------
-    float mx = -INFINITY;
+  for (int off = 1; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off));
+  if (lane == 0) wg_max[wave] = wmax;
+  __syncthreads();
+  const int gmax = max(max(wg_max[0], wg_max[1]), max(wg_max[2], wg_max[3]));
+  if (gmax < k_lo) return;                                   // whole workgroup: nobody looks into this unit
+  const int k_hi = min(gmax + 1, k_lo + UNIT);               // exclusive; <= L + n
+  const int n_stages = (k_hi - k_lo + STAGE - 1) / STAGE;
+  const int first_blk = k_lo >> 4, last_blk = (k_hi - 1) >> 4;
+
+  // physical ids of this unit's blocks, one or two per lane; blocks past the last needed one are
+  // replaced by it (their data is fetched but every key in them is masked)
+  const int ids0 = bt[min(first_blk + lane, last_blk)];
+  const int ids1 = SUPER ? bt[min(first_blk + 64 + lane, last_blk)] : 0;
+
+  Frag qf[CB][DK];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+  for (int cb = 0; cb < CB; ++cb) {
+    // row blocks past r_pad (grid padding) read the last real block instead; their rows are dead anyway
+    const int rb = min(row[cb] >> 4, r_pad / 16 - 1);
+    const uint16_t* qb = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)rb * DK * 512;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int kpos = k0 + b * 16 + g * 4 + e;
-        const float v = kpos <= qpos ? sc[b][e] * scale_log2 : -INFINITY;
-        sc[b][e] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-    // ---- exponentials, row sum in a fixed tree ----------------------------------------
-    float rs = 0.f;
+    for (int d = 0; d < DK; ++d) qf[cb][d].u = *(const uint4*)(qb + d * 512 + lane * 8);
+  }
+
+  // each wave fetches two of the eight blocks of a stage, straight from global memory into LDS
+  // (no staging registers): one instruction moves 1 KiB, lane i's 16 bytes landing at base + 16 i
+#define ATT_FETCH(st_, buf_)                                                                   \
+  do {                                                                                         \
+    const int bj_ = (st_) * 8 + wave * 2;               /* block index inside the unit */      \
+    const int id0_ = __shfl(bj_ < 64 ? ids0 : ids1, bj_ & 63);                                 \
+    const int id1_ = __shfl(bj_ + 1 < 64 ? ids0 : ids1, (bj_ + 1) & 63);                       \
+    tile_to_lds<TL>(&lds_k[buf_][(wave * 2) * TV4], k_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);     \
+    tile_to_lds<TL>(&lds_v[buf_][(wave * 2) * TV4], v_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);     \
+    tile_to_lds<TL>(&lds_k[buf_][(wave * 2 + 1) * TV4], k_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane); \
+    tile_to_lds<TL>(&lds_v[buf_][(wave * 2 + 1) * TV4], v_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane); \
+  } while (0)
+  // all of this wave's outstanding fetches have landed in LDS
+#define ATT_LANDED() __builtin_amdgcn_s_waitcnt(0x0F70) /* vmcnt(0) */
+
+  float m[CB], l[CB];
+  f32x4 acc[CB][DB];
+  float sm[CB], sl[CB];                                      // super mode: running fold of finished chunks
+  f32x4 sacc[CB][DB];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+  for (int cb = 0; cb < CB; ++cb) {
+    m[cb] = -INFINITY;
+    l[cb] = 0.f;
+    sm[cb] = -INFINITY;
+    sl[cb] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) sc[b][e] = __builtin_amdgcn_exp2f(sc[b][e] - m_use);
-      rs += ((sc[b][0] + sc[b][1]) + sc[b][2]) + sc[b][3];
-    }
-    rs += __shfl_xor(rs, 16);
-    rs += __shfl_xor(rs, 32);
-    l = l * alpha + rs;
-    m = m_new;
-#pragma unroll
-    for (int d = 0; d < DB; ++d) acc[d] *= alpha;
-    // ---- acc^T[feature][query] += V^T P^T, 32 keys per MFMA ----------------------------
-    // k-slot e of lane group g is key g*4+e of the first block (e < 4) or of the second (e >= 4);
-    // P and V use the same assignment.
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      if (blk[2 * kk] < 0) continue;   // wave-uniform: both blocks beyond k_end
-      Frag pf;
-      pf.h[0].x = pack2_bf16(sc[2 * kk][0], sc[2 * kk][1]);
-      pf.h[0].y = pack2_bf16(sc[2 * kk][2], sc[2 * kk][3]);
-      pf.h[1].x = pack2_bf16(sc[2 * kk + 1][0], sc[2 * kk + 1][1]);
-      pf.h[1].y = pack2_bf16(sc[2 * kk + 1][2], sc[2 * kk + 1][3]);
-      const uint16_t* vt0 = v_plane + ((size_t)blk[2 * kk] * n_kv_heads + kvh) * 16 * HD;
-      const bool has1 = blk[2 * kk + 1] >= 0;
-      const uint16_t* vt1 = v_plane + ((size_t)(has1 ? blk[2 * kk + 1] : blk[2 * kk]) * n_kv_heads + kvh) * 16 * HD;
-      // slots at or beyond `total` hold stale or never-written data: force them to zero so that
-      // 0 * garbage cannot produce a NaN
-      const int kp0 = k0 + kk * 32 + g * 4, kp1 = kp0 + 16;
-#pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        Frag vf;
-        vf.h[0] = *(const uint2*)(vt0 + (d * 16 + col) * 16 + g * 4);
-        vf.h[1] = has1 ? *(const uint2*)(vt1 + (d * 16 + col) * 16 + g * 4) : make_uint2(0, 0);
-        if (kp0 + 3 >= total) {
-          if (kp0 + 0 >= total) vf.h[0].x &= 0xFFFF0000u;
-          if (kp0 + 1 >= total) vf.h[0].x &= 0x0000FFFFu;
-          if (kp0 + 2 >= total) vf.h[0].y &= 0xFFFF0000u;
-          if (kp0 + 3 >= total) vf.h[0].y &= 0x0000FFFFu;
-        }
-        if (kp1 + 3 >= total) {
-          if (kp1 + 0 >= total) vf.h[1].x &= 0xFFFF0000u;
-          if (kp1 + 1 >= total) vf.h[1].x &= 0x0000FFFFu;
-          if (kp1 + 2 >= total) vf.h[1].y &= 0xFFFF0000u;
-          if (kp1 + 3 >= total) vf.h[1].y &= 0x0000FFFFu;
-        }
-        acc[d] = mfma16(vf.v, pf.v, acc[d]);
-      }
+    for (int d = 0; d < DB; ++d) {
+      acc[cb][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      sacc[cb][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
   }
 
-  // ---- partial (m, l, acc) of this super-chunk for every row that reaches into it ------
-  if (qpos >= k_begin) {
-    const size_t prow = (((size_t)s * n_kv_heads + kvh) * n_super + c) * r_pad + r;
+  ATT_FETCH(0, 0);
+  ATT_LANDED();
+  __syncthreads();
+  for (int st = 0; st < n_stages; ++st) {
+    const int buf = st & 1;
+    if (st + 1 < n_stages) ATT_FETCH(st + 1, buf ^ 1);
+    const uint16_t* vbase = (const uint16_t*)lds_v[buf];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int k0 = k_lo + st * STAGE + s2 * STEP;
+      if (k0 >= k_hi) break;                                  // workgroup-uniform
+      // ---- scores of 4 blocks of 16 keys: S^T[key][query] ---------------------------------
+      f32x4 sc[CB][4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) sc[cb][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (k0 + b * 16 < k_hi) {                            // workgroup-uniform
+#pragma unroll
+          for (int d = 0; d < DK; ++d) {
+            Frag kf;
+            kf.u = lds_k[buf][(s2 * 4 + b) * TV4 + d * 64 + lane];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) sc[cb][b] = mfma16(kf.v, qf[cb][d].v, sc[cb][b]);
+          }
+        }
+      }
+      // ---- mask, online softmax state, P in bf16 ------------------------------------------
+      Frag pf[CB][2];
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int kpos = k0 + b * 16 + g * 4 + e;
+            const float v = kpos <= qpos[cb] ? sc[cb][b][e] * scale_log2 : -INFINITY;
+            sc[cb][b][e] = v;
+            mx = fmaxf(mx, v);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m[cb], mx);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m[cb] - m_use);
+        float rs = 0.f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sc[cb][b][e] = __builtin_amdgcn_exp2f(sc[cb][b][e] - m_use);
+          rs += ((sc[cb][b][0] + sc[cb][b][1]) + sc[cb][b][2]) + sc[cb][b][3];
+        }
+        rs += __shfl_xor(rs, 16);
+        rs += __shfl_xor(rs, 32);
+        l[cb] = l[cb] * alpha + rs;
+        m[cb] = m_new;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
+        // k-slot e of lane group g is key g*4+e of the first block of a pair (e < 4) or of the
+        // second (e >= 4); V below uses the same assignment
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          pf[cb][kk].h[0].x = pack2_bf16(sc[cb][2 * kk][0], sc[cb][2 * kk][1]);
+          pf[cb][kk].h[0].y = pack2_bf16(sc[cb][2 * kk][2], sc[cb][2 * kk][3]);
+          pf[cb][kk].h[1].x = pack2_bf16(sc[cb][2 * kk + 1][0], sc[cb][2 * kk + 1][1]);
+          pf[cb][kk].h[1].y = pack2_bf16(sc[cb][2 * kk + 1][2], sc[cb][2 * kk + 1][3]);
+        }
+      }
+      // ---- acc^T[feature][query] += V^T P^T, 32 keys per MFMA ------------------------------
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const int kp0 = k0 + kk * 32 + g * 4, kp1 = kp0 + 16;
+        if (k0 + kk * 32 >= k_hi) break;                      // workgroup-uniform
+        const uint16_t* vt0 = vbase + (size_t)(s2 * 4 + 2 * kk) * TV4 * 8;
+        const uint16_t* vt1 = vt0 + TV4 * 8;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          Frag vf;
+          vf.h[0] = *(const uint2*)(vt0 + (d * 16 + col) * 16 + g * 4);
+          vf.h[1] = *(const uint2*)(vt1 + (d * 16 + col) * 16 + g * 4);
+          // slots at or beyond k_hi hold stale, never-written or foreign data: force them to zero
+          // so that 0 * garbage cannot produce a NaN
+          if (kp0 + 3 >= k_hi) {
+            if (kp0 + 0 >= k_hi) vf.h[0].x &= 0xFFFF0000u;
+            if (kp0 + 1 >= k_hi) vf.h[0].x &= 0x0000FFFFu;
+            if (kp0 + 2 >= k_hi) vf.h[0].y &= 0xFFFF0000u;
+            if (kp0 + 3 >= k_hi) vf.h[0].y &= 0x0000FFFFu;
+          }
+          if (kp1 + 3 >= k_hi) {
+            if (kp1 + 0 >= k_hi) vf.h[1].x &= 0xFFFF0000u;
+            if (kp1 + 1 >= k_hi) vf.h[1].x &= 0x0000FFFFu;
+            if (kp1 + 2 >= k_hi) vf.h[1].y &= 0xFFFF0000u;
+            if (kp1 + 3 >= k_hi) vf.h[1].y &= 0x0000FFFFu;
+          }
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb) acc[cb][d] = mfma16(vf.v, pf[cb][kk].v, acc[cb][d]);
+        }
+      }
+    }
+    if (SUPER && ((st & 1) || st + 1 == n_stages)) {
+      // a chunk is complete: fold it into the running super partial and start the next one afresh
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        if (st < 2) {
+          sm[cb] = m[cb];
+          sl[cb] = l[cb];
+#pragma unroll
+          for (int d = 0; d < DB; ++d) sacc[cb][d] = acc[cb][d];
+        } else {
+          fold<DB>(sm[cb], sl[cb], sacc[cb], m[cb], l[cb], acc[cb]);
+        }
+        m[cb] = -INFINITY;
+        l[cb] = 0.f;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) acc[cb][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+    }
+    ATT_LANDED();
+    __syncthreads();
+  }
+
+  // ---- partial of this unit for every row that reaches into it ---------------------------------
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    if (qpos[cb] < k_lo) continue;
+    const size_t prow = (((size_t)s * n_kv_heads + kvh) * n_units + unit) * r_pad + row[cb];
     float* pa = part_acc + prow * HD;
 #pragma unroll
-    for (int d = 0; d < DB; ++d) *(f32x4*)(pa + d * 16 + g * 4) = acc[d];
-    if (g == 0) *(float2*)(part_ml + prow * 2) = make_float2(m, l);
+    for (int d = 0; d < DB; ++d) *(f32x4*)(pa + d * 16 + g * 4) = SUPER ? sacc[cb][d] : acc[cb][d];
+    if (g == 0) *(float2*)(part_ml + prow * 2) = SUPER ? make_float2(sm[cb], sl[cb]) : make_float2(m[cb], l[cb]);
   }
 }
 
-// Fold the super-chunk partials of every query row in ascending order and write
-// the normalised output, bf16, into the tile layout of the O-projection's
-// activation operand.  One thread per (row, 4 features).
-template <int HD>
+#undef ATT_FETCH
+#undef ATT_LANDED
+
+// Fold the partials of every query row (chunks inside a super left to right, then the supers
+// left to right) and write the normalised output, bf16, into the tile layout of the
+// O-projection's activation operand.  One thread per (row, 4 features).
+template <int HD, bool SUPER>
 __global__ void attention_merge_kernel(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
                                        const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
-                                       int n_kv_heads, int group, int window, int r_pad, int n_super, int d_attn,
+                                       int n_kv_heads, int group, int window, int r_pad, int n_units, int d_attn,
                                        uint16_t* __restrict__ out) {
   constexpr int QUADS = HD / 4;
   const int quad = threadIdx.x % QUADS;
@@ -192,29 +307,88 @@ __global__ void attention_merge_kernel(const float* __restrict__ part_acc, const
     *dst = make_uint2(0, 0);
     return;
   }
-  const int last = (L + i) / LLM42_SUPERCHUNK;
-  const size_t base = ((size_t)s * n_kv_heads + kvh) * n_super;
-  size_t prow = base * r_pad + r;
-  float2 ml = *(const float2*)(part_ml + prow * 2);
-  float M = ml.x, Ls = ml.y;
-  f32x4 A = *(const f32x4*)(part_acc + prow * HD + quad * 4);
-  for (int c = 1; c <= last; ++c) {
-    prow = (base + c) * r_pad + r;
-    ml = *(const float2*)(part_ml + prow * 2);
-    const f32x4 B = *(const f32x4*)(part_acc + prow * HD + quad * 4);
-    const float mn = fmaxf(M, ml.x);
-    const float a = __builtin_amdgcn_exp2f(M - mn), b = __builtin_amdgcn_exp2f(ml.x - mn);
-    Ls = Ls * a + ml.y * b;
-    A = A * a + B * b;
-    M = mn;
+  const size_t base = ((size_t)s * n_kv_heads + kvh) * n_units;
+  auto slot_ml = [&](int u) { return *(const float2*)(part_ml + ((base + u) * r_pad + r) * 2); };
+  auto slot_acc = [&](int u) { return *(const f32x4*)(part_acc + ((base + u) * r_pad + r) * HD + quad * 4); };
+  float M, Ls;
+  f32x4 A[1];
+  if (SUPER) {
+    const int last = (L + i) / SUPER_KEYS;
+    float2 ml = slot_ml(0);
+    M = ml.x;
+    Ls = ml.y;
+    A[0] = slot_acc(0);
+    for (int u = 1; u <= last; ++u) {
+      ml = slot_ml(u);
+      const f32x4 B[1] = {slot_acc(u)};
+      fold<1>(M, Ls, A, ml.x, ml.y, B);
+    }
+  } else {
+    constexpr int PER = SUPER_KEYS / CHUNK;
+    const int last = (L + i) / CHUNK;
+    M = 0.f;
+    Ls = 0.f;
+    A[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 <= last; c0 += PER) {
+      float2 ml = slot_ml(c0);
+      float m2 = ml.x, l2 = ml.y;
+      f32x4 a2[1] = {slot_acc(c0)};
+      for (int c = c0 + 1; c <= min(c0 + PER - 1, last); ++c) {
+        ml = slot_ml(c);
+        const f32x4 B[1] = {slot_acc(c)};
+        fold<1>(m2, l2, a2, ml.x, ml.y, B);
+      }
+      if (c0 == 0) {
+        M = m2;
+        Ls = l2;
+        A[0] = a2[0];
+      } else {
+        fold<1>(M, Ls, A, m2, l2, a2);
+      }
+    }
   }
   uint2 o;
-  o.x = pack2_bf16(A[0] / Ls, A[1] / Ls);
-  o.y = pack2_bf16(A[2] / Ls, A[3] / Ls);
+  o.x = pack2_bf16(A[0][0] / Ls, A[0][1] / Ls);
+  o.y = pack2_bf16(A[0][2] / Ls, A[0][3] / Ls);
   *dst = o;
 }
 
+template <int HD, int CB, bool SUPER>
+void launch_one(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
+                int window, const Workspace& ws, hipStream_t st) {
+  const llm42_config& c = m->cfg;
+  const float scale_log2 = (1.0f / sqrtf((float)c.head_dim)) * 1.44269504088896340736f;
+  const int col_blocks = ws.r_pad / 16;
+  const dim3 grid(ws.attn_units, (col_blocks + 4 * CB - 1) / (4 * CB), num_seqs * c.n_kv_heads);
+  attention_kernel<HD, CB, SUPER><<<grid, 256, 0, st>>>(ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table,
+                                                        ws.seq_len, ws.seq_n, c.n_kv_heads, m->group, window, ws.r_pad,
+                                                        kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc,
+                                                        ws.part_ml);
+  const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
+  attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
+                                      0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
+                                               window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
+}
+
+template <int HD>
+void launch_hd(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
+               int window, const Workspace& ws, hipStream_t st) {
+  const bool two = ws.r_pad / 16 >= 8;
+  if (ws.attn_super) {
+    if (two) launch_one<HD, 2, true>(m, kp, vp, kv, num_seqs, window, ws, st);
+    else launch_one<HD, 1, true>(m, kp, vp, kv, num_seqs, window, ws, st);
+  } else {
+    if (two) launch_one<HD, 2, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    else launch_one<HD, 1, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+  }
+}
+
 }  // namespace
+
+int attention_units(bool super_mode, int max_context) {
+  const int keys = super_mode ? SUPER_KEYS : CHUNK;
+  return (max_context + keys - 1) / keys;
+}
 
 void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv, int num_seqs, int window,
                       int max_context, const Workspace& ws, hipStream_t st) {
@@ -222,25 +396,6 @@ void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv,
   const size_t plane = (size_t)kv->num_blocks * c.n_kv_heads * 16 * c.head_dim;
   const uint16_t* kp = (const uint16_t*)kv->kv_base + ((size_t)layer * 2 + 0) * plane;
   const uint16_t* vp = (const uint16_t*)kv->kv_base + ((size_t)layer * 2 + 1) * plane;
-  const float scale_log2 = (1.0f / sqrtf((float)c.head_dim)) * 1.44269504088896340736f;
-  const int n_super = (max_context + LLM42_SUPERCHUNK - 1) / LLM42_SUPERCHUNK;   // == ws.n_super
-  const dim3 grid(n_super, (ws.r_pad / 16 + 3) / 4, num_seqs * c.n_kv_heads);
-  const int rows = m->group * window;
-  if (c.head_dim == 128) {
-    attention_kernel<128><<<grid, 256, 0, st>>>(ws.q, kp, vp, kv->block_table, ws.seq_len, ws.seq_n, c.n_kv_heads,
-                                                m->group, window, ws.r_pad, kv->max_blocks_per_seq, ws.n_super,
-                                                scale_log2, ws.part_acc, ws.part_ml);
-    const int rows_per_block = 256 / 32;
-    attention_merge_kernel<128><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
-                                  0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
-                                           window, ws.r_pad, ws.n_super, m->d_attn, ws.attn);
-  } else {
-    attention_kernel<64><<<grid, 256, 0, st>>>(ws.q, kp, vp, kv->block_table, ws.seq_len, ws.seq_n, c.n_kv_heads,
-                                               m->group, window, ws.r_pad, kv->max_blocks_per_seq, ws.n_super,
-                                               scale_log2, ws.part_acc, ws.part_ml);
-    const int rows_per_block = 256 / 16;
-    attention_merge_kernel<64><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
-                                 0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
-                                          window, ws.r_pad, ws.n_super, m->d_attn, ws.attn);
-  }
+  if (c.head_dim == 128) launch_hd<128>(m, kp, vp, kv, num_seqs, window, ws, st);
+  else launch_hd<64>(m, kp, vp, kv, num_seqs, window, ws, st);
 }

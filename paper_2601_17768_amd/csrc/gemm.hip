@@ -114,26 +114,33 @@ struct LogitsEpi {
   }
 };
 
-// Streaming kernel: every wave owns one block of 16 features and MB blocks of 16
-// tokens, reads its weight tiles once, straight from HBM into registers (1 KiB
-// per load instruction, fully coalesced thanks to the tile layout), and its
-// activation tiles through the caches.  4 waves per workgroup, no LDS, no barrier.
-template <int MB, class Epi>
+// ---------------------------------------------------------------------------------------------
+// Split of the reduction dimension.  A GEMM with SPLIT == 2 has TWO accumulators per output
+// element: p0 over k-tiles [0, h) and p1 over k-tiles [h, k_tiles), h = (k_tiles + 1) / 2, each
+// started at zero and advanced in ascending k; the result is p0 + p1 (one fp32 add).  Which GEMMs
+// are split is fixed per layer type below and never depends on the number of rows.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline int split_point(int k_tiles) { return (k_tiles + 1) / 2; }
+
+// Large-batch fallback: every wave owns one block of 16 features and MB blocks of 16 tokens and
+// walks k-tiles [k_begin, k_begin + k_count).  With ADD_PARTIAL the fp32 partial of the other
+// half (stored earlier by the same kernel with a StorePartialEpi) is added before the epilogue.
+template <int MB, bool ADD_PARTIAL, class Epi>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
-                                                          int n_blocks, int k_tiles, Epi epi) {
+                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
+                                                          const float* __restrict__ partial, int n, Epi epi) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nb = blockIdx.x * 4 + wave;
   if (nb >= n_blocks) return;
   const int mb0 = blockIdx.y * MB;
-  const bf16x8* wp = w + (size_t)nb * k_tiles * 64 + lane;
-  const bf16x8* xp = x + (size_t)mb0 * k_tiles * 64 + lane;
+  const bf16x8* wp = w + ((size_t)nb * k_tiles + k_begin) * 64 + lane;
+  const bf16x8* xp = x + ((size_t)mb0 * k_tiles + k_begin) * 64 + lane;
   f32x4 acc[MB];
 #pragma unroll
   for (int b = 0; b < MB; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  // U weight tiles are requested before the first of them is used; the MFMA order stays k ascending
   constexpr int U = 8;
   int kt = 0;
-  for (; kt + U <= k_tiles; kt += U) {
+  for (; kt + U <= k_count; kt += U) {
     bf16x8 a[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(wp + (size_t)(kt + u) * 64);
@@ -142,82 +149,210 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const bf16x8* __restri
 #pragma unroll
       for (int b = 0; b < MB; ++b) acc[b] = mfma16(a[u], xp[((size_t)b * k_tiles + kt + u) * 64], acc[b]);
   }
-  for (; kt < k_tiles; ++kt) {
+  for (; kt < k_count; ++kt) {
     const bf16x8 a = __builtin_nontemporal_load(wp + (size_t)kt * 64);
 #pragma unroll
     for (int b = 0; b < MB; ++b) acc[b] = mfma16(a, xp[((size_t)b * k_tiles + kt) * 64], acc[b]);
   }
 #pragma unroll
-  for (int b = 0; b < MB; ++b) epi(nb, lane, (mb0 + b) * 16 + (lane & 15), acc[b]);
+  for (int b = 0; b < MB; ++b) {
+    const int row = (mb0 + b) * 16 + (lane & 15);
+    if (ADD_PARTIAL) acc[b] = acc[b] + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
+    epi(nb, lane, row, acc[b]);
+  }
 }
 
-// Small-batch kernel (at most 64 tokens): HBM-bound weight streaming.
-// One workgroup of 4 waves per block of 16 features.  All 4 waves fetch the
-// block's weight tiles, CH k-tiles per round (CH KiB in flight per workgroup,
-// each wave fetching every 4th tile), and park them in LDS; waves 0 .. MB-1 then
-// each advance one 16-token block's accumulator through the round's tiles in
-// ascending k order, with their own activation tiles prefetched in registers.
-// The next round's weight loads are issued before the current round is consumed.
-// Only the fetch is spread over the waves: the accumulation order per output
-// element is the one stated at the top of this file.
-template <int MB, class Epi>
-__global__ __launch_bounds__(256) void gemm_coop_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
-                                                        int k_tiles, Epi epi) {
+struct StorePartialEpi {
+  float* partial;   // [m_pad][n] in the residual-stream layout
+  int n;
+  __device__ void operator()(int nb, int lane, int row, const f32x4 acc) const {
+    *(f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n)) = acc;
+  }
+};
+
+// Small-batch kernel for narrow outputs (at most 64 tokens): HBM-bound weight streaming with one
+// workgroup per block of 16 features, so that every CU streams.  SPLIT groups of 4 waves each own
+// one half of the k range.  Inside a group all 4 waves fetch the block's weight tiles, CH k-tiles
+// per round (each wave every 4th tile), and park them in LDS; waves 0 .. MB-1 of the group then
+// each advance one 16-token block's accumulator through the round's tiles in ascending k, with
+// their own activation tiles prefetched in registers.  The next round's weight loads are issued
+// before the current round is consumed.  Only the fetch is spread over the waves; the accumulation
+// order per output element is the one stated above.
+template <int MB, int SPLIT, class Epi>
+__global__ __launch_bounds__(256 * SPLIT) void gemm_coop_kernel(const bf16x8* __restrict__ w,
+                                                                const bf16x8* __restrict__ x, int k_tiles, Epi epi) {
   constexpr int CH = 32;
-  __shared__ bf16x8 wlds[CH * 64];
+  __shared__ bf16x8 wlds[SPLIT][CH * 64];
+  __shared__ f32x4 merge[MB][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int grp = wave >> 2, gw = wave & 3;
   const int nb = blockIdx.x;
-  const bf16x8* wp = w + (size_t)nb * k_tiles * 64 + lane;
-  const bf16x8* xp = x + (size_t)wave * k_tiles * 64 + lane;   // consumer `wave` owns token block `wave`
-  const bool consumer = wave < MB;
+  const int h = SPLIT == 2 ? split_point(k_tiles) : k_tiles;
+  const int k_begin = grp == 0 ? 0 : h;
+  const int k_count = grp == 0 ? h : k_tiles - h;
+  const int my_rounds = k_count / CH;                // full rounds of this group; the rest is the tail
+  const int rounds = h / CH;                         // group 0 never has fewer than group 1
+  const bf16x8* wp = w + ((size_t)nb * k_tiles + k_begin) * 64 + lane;
+  const bf16x8* xp = x + ((size_t)gw * k_tiles + k_begin) * 64 + lane;   // consumer gw owns token block gw
+  const bool consumer = gw < MB;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   bf16x8 wr[CH / 4], xr[CH];
+  // no load below sits behind a per-load condition: the compiler would serialise such loads
+  if (my_rounds > 0) {
 #pragma unroll
-  for (int i = 0; i < CH / 4; ++i)
-    if (i * 4 + wave < k_tiles) wr[i] = __builtin_nontemporal_load(wp + (size_t)(i * 4 + wave) * 64);
-  if (consumer) {
-#pragma unroll
-    for (int j = 0; j < CH; ++j)
-      if (j < k_tiles) xr[j] = xp[(size_t)j * 64];
-  }
-  for (int c0 = 0; c0 < k_tiles; c0 += CH) {
-    const int nt = min(CH, k_tiles - c0);
-#pragma unroll
-    for (int i = 0; i < CH / 4; ++i)
-      if (i * 4 + wave < nt) wlds[(i * 4 + wave) * 64 + lane] = wr[i];
-    __syncthreads();
-    const int n1 = c0 + CH;   // first tile of the next round
-#pragma unroll
-    for (int i = 0; i < CH / 4; ++i)
-      if (n1 + i * 4 + wave < k_tiles) wr[i] = __builtin_nontemporal_load(wp + (size_t)(n1 + i * 4 + wave) * 64);
+    for (int i = 0; i < CH / 4; ++i) wr[i] = __builtin_nontemporal_load(wp + (size_t)(i * 4 + gw) * 64);
     if (consumer) {
 #pragma unroll
-      for (int j = 0; j < CH; ++j)
-        if (j < nt) acc = mfma16(wlds[j * 64 + lane], xr[j], acc);
+      for (int j = 0; j < CH; ++j) xr[j] = xp[(size_t)j * 64];
+    }
+  }
+  for (int r = 0; r < rounds; ++r) {
+    const bool live = r < my_rounds, more = r + 1 < my_rounds;
+    if (live) {
 #pragma unroll
-      for (int j = 0; j < CH; ++j)
-        if (n1 + j < k_tiles) xr[j] = xp[(size_t)(n1 + j) * 64];
+      for (int i = 0; i < CH / 4; ++i) wlds[grp][(i * 4 + gw) * 64 + lane] = wr[i];
+    }
+    __syncthreads();
+    const bf16x8* wn = wp + (size_t)(r + 1) * CH * 64;
+    const bf16x8* xn = xp + (size_t)(r + 1) * CH * 64;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < CH / 4; ++i) wr[i] = __builtin_nontemporal_load(wn + (size_t)(i * 4 + gw) * 64);
+    }
+    if (consumer && live) {
+#pragma unroll
+      for (int j = 0; j < CH; ++j) acc = mfma16(wlds[grp][j * 64 + lane], xr[j], acc);
+      if (more) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) xr[j] = xn[(size_t)j * 64];
+      }
     }
     __syncthreads();
   }
-  if (consumer) epi(nb, lane, wave * 16 + (lane & 15), acc);
+  if (consumer) {   // tail of fewer than CH tiles (model dimensions that are no multiple of 1024): tile by tile
+    for (int kt = my_rounds * CH; kt < k_count; ++kt) acc = mfma16(wp[(size_t)kt * 64], xp[(size_t)kt * 64], acc);
+  }
+  if (SPLIT == 2) {
+    if (consumer && grp == 1) merge[gw][lane] = acc;
+    __syncthreads();
+    if (consumer && grp == 0) acc = acc + merge[gw][lane];
+  }
+  if (consumer && grp == 0) epi(nb, lane, gw * 16 + (lane & 15), acc);
 }
 
-template <class Epi>
-void launch_stream(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padded, int m_pad, const Epi& epi,
-                   hipStream_t st) {
-  const int k_tiles = k_padded / 32;
+// Small-batch kernel for wide outputs (at most 64 tokens): 8 waves per workgroup, every wave owns
+// its own block of 16 features and streams that block's weight tiles from HBM into registers, one
+// round (CH k-tiles) ahead of their use.  The activation tiles, which all 8 waves need, are fetched
+// once per workgroup and shared through LDS (double buffered), which cuts the L2 traffic for
+// activations by 8.  Accumulation order per output element: as stated above.
+template <int MB, class Epi>
+__global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
+                                                          int n_blocks, int k_tiles, Epi epi) {
+  constexpr int CH = 16, NW = 8;
+  constexpr int XT = MB * CH / NW;                   // activation tiles each wave fetches per round
+  __shared__ bf16x8 xlds[2][MB * CH * 64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nb = min(blockIdx.x * NW + wave, n_blocks - 1);   // surplus waves redo the last block, discarded below
+  const bool owner = blockIdx.x * NW + wave < n_blocks;
+  const bf16x8* wp = w + (size_t)nb * k_tiles * 64 + lane;
+  const bf16x8* xp = x + lane;
+  f32x4 acc[MB];
+#pragma unroll
+  for (int b = 0; b < MB; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  bf16x8 wa[CH], wb[CH], xg[XT];
+  const int rounds = k_tiles / CH;                   // full rounds; the rest is the tail
+
+  // none of these loads sits behind a per-load condition (the compiler would serialise them)
+  auto load_w = [&](bf16x8(&dst)[CH], int r) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j) dst[j] = __builtin_nontemporal_load(wp + (size_t)(r * CH + j) * 64);
+  };
+  auto load_x = [&](int r) {   // tile q of the round: token block q / CH, k-tile r * CH + q % CH
+#pragma unroll
+    for (int i = 0; i < XT; ++i) {
+      const int q = i * NW + wave;
+      xg[i] = xp[((size_t)(q / CH) * k_tiles + r * CH + q % CH) * 64];
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < XT; ++i) xlds[buf][(i * NW + wave) * 64 + lane] = xg[i];
+  };
+  auto compute = [&](const bf16x8(&cur)[CH], int buf) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+#pragma unroll
+      for (int b = 0; b < MB; ++b) acc[b] = mfma16(cur[j], xlds[buf][(b * CH + j) * 64 + lane], acc[b]);
+  };
+
+  if (rounds > 0) {
+    load_w(wa, 0);
+    load_x(0);
+    store_x(0);
+  }
+  __syncthreads();
+  for (int r = 0; r < rounds; r += 2) {
+    // even round: consume wa / buffer 0 while wb / buffer 1 are in flight
+    if (r + 1 < rounds) {
+      load_w(wb, r + 1);
+      load_x(r + 1);
+    }
+    compute(wa, 0);
+    if (r + 1 < rounds) store_x(1);
+    __syncthreads();
+    if (r + 1 >= rounds) break;
+    if (r + 2 < rounds) {
+      load_w(wa, r + 2);
+      load_x(r + 2);
+    }
+    compute(wb, 1);
+    if (r + 2 < rounds) store_x(0);
+    __syncthreads();
+  }
+  for (int kt = rounds * CH; kt < k_tiles; ++kt) {   // tail of fewer than CH tiles: tile by tile
+    const bf16x8 a = wp[(size_t)kt * 64];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) acc[b] = mfma16(a, xp[((size_t)b * k_tiles + kt) * 64], acc[b]);
+  }
+  if (owner) {
+#pragma unroll
+    for (int b = 0; b < MB; ++b) epi(nb, lane, b * 16 + (lane & 15), acc[b]);
+  }
+}
+
+enum GemmKind { GEMM_QKV = 0, GEMM_RESIDUAL = 1, GEMM_GATE_UP = 2, GEMM_LOGITS = 3 };
+// The split of each GEMM type (part of the reduction schedule, see above).
+constexpr int kSplit[4] = {1, 2, 1, 1};
+
+template <int SPLIT, class Epi>
+void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padded, int n, const Workspace& ws,
+                 bool wide, const Epi& epi, hipStream_t st) {
+  const int k_tiles = k_padded / 32, m_pad = ws.m_pad;
   const bf16x8* wp = (const bf16x8*)w;
   const bf16x8* xp = (const bf16x8*)x;
-  if (m_pad == 16) {
-    gemm_coop_kernel<1, Epi><<<n_blocks, 256, 0, st>>>(wp, xp, k_tiles, epi);
-  } else if (m_pad == 32) {
-    gemm_coop_kernel<2, Epi><<<n_blocks, 256, 0, st>>>(wp, xp, k_tiles, epi);
-  } else if (m_pad == 64) {
-    gemm_coop_kernel<4, Epi><<<n_blocks, 256, 0, st>>>(wp, xp, k_tiles, epi);
-  } else {   // m_pad is a multiple of 64
-    const unsigned gx = (unsigned)((n_blocks + 3) / 4);
-    gemm_stream_kernel<4, Epi><<<dim3(gx, m_pad / 64), 256, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+  if (m_pad <= 64) {
+    if (wide && SPLIT == 1) {
+      const unsigned gx = (unsigned)((n_blocks + 7) / 8);
+      if (m_pad == 16) gemm_xshare_kernel<1, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+      else if (m_pad == 32) gemm_xshare_kernel<2, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+      else gemm_xshare_kernel<4, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+    } else {
+      if (m_pad == 16) gemm_coop_kernel<1, SPLIT, Epi><<<n_blocks, 256 * SPLIT, 0, st>>>(wp, xp, k_tiles, epi);
+      else if (m_pad == 32) gemm_coop_kernel<2, SPLIT, Epi><<<n_blocks, 256 * SPLIT, 0, st>>>(wp, xp, k_tiles, epi);
+      else gemm_coop_kernel<4, SPLIT, Epi><<<n_blocks, 256 * SPLIT, 0, st>>>(wp, xp, k_tiles, epi);
+    }
+    return;
+  }
+  // m_pad is a multiple of 64
+  const dim3 grid((unsigned)((n_blocks + 3) / 4), m_pad / 64);
+  if (SPLIT == 1) {
+    gemm_stream_kernel<4, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr, n, epi);
+  } else {
+    const int h = split_point(k_tiles);
+    StorePartialEpi pe{ws.split_part, n};
+    gemm_stream_kernel<4, false, StorePartialEpi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, h, k_tiles - h,
+                                                                        nullptr, n, pe);
+    gemm_stream_kernel<4, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part, n, epi);
   }
 }
 
@@ -242,18 +377,18 @@ void launch_gemm_qkv(const llm42_model* m, int layer, const llm42_kv_cache* kv, 
   e.window = window;
   e.r_pad = ws.r_pad;
   e.max_blocks_per_seq = kv->max_blocks_per_seq;
-  launch_stream(m->layers[layer].wqkv, ws.normed, m->n_qkv / 16, c.d_model, ws.m_pad, e, st);
+  launch_gemm<kSplit[GEMM_QKV]>(m->layers[layer].wqkv, ws.normed, m->n_qkv / 16, c.d_model, m->n_qkv, ws, false, e, st);
 }
 
 void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, int n, int k_padded,
                           const Workspace& ws, hipStream_t st) {
   ResidualEpi e{resid, n};
-  launch_stream(w, x, n / 16, k_padded, ws.m_pad, e, st);
+  launch_gemm<kSplit[GEMM_RESIDUAL]>(w, x, n / 16, k_padded, n, ws, false, e, st);
 }
 
 void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hipStream_t st) {
   SwigluEpi e{ws.hidden, m->ffn_k};
-  launch_stream(m->layers[layer].wgu, ws.normed, m->gu_blocks, m->cfg.d_model, ws.m_pad, e, st);
+  launch_gemm<kSplit[GEMM_GATE_UP]>(m->layers[layer].wgu, ws.normed, m->gu_blocks, m->cfg.d_model, m->gu_blocks * 16, ws, true, e, st);
 }
 
 void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const Workspace& ws, hipStream_t st) {
@@ -266,5 +401,5 @@ void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, con
   e.window = window;
   e.vocab = m->cfg.vocab;
   e.n_blocks = m->cfg.vocab / 16;
-  launch_stream(m->lm_head, ws.normed, m->cfg.vocab / 16, m->cfg.d_model, ws.m_pad, e, st);
+  launch_gemm<kSplit[GEMM_LOGITS]>(m->lm_head, ws.normed, m->cfg.vocab / 16, m->cfg.d_model, m->cfg.vocab, ws, true, e, st);
 }

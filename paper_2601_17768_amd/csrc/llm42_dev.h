@@ -24,8 +24,6 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-#define LLM42_SUPERCHUNK 1024  // keys per attention partial (anchored at absolute positions)
-#define LLM42_KEYSTEP 64       // keys per online-softmax step inside a partial
 
 __host__ __device__ inline size_t pk_off(int r, int c, int c_padded) {
   return ((size_t)(r >> 4) * (size_t)(c_padded >> 5) + (size_t)(c >> 5)) * 512 +
@@ -81,11 +79,13 @@ struct Workspace {
   int m_rows;     // num_seqs * window
   int m_pad;      // rows padded for the GEMM grid
   int r_pad;      // query rows per (seq, kv head) padded to 16
-  int n_super;    // attention partials per row
+  int attn_units; // attention partial slots per row (chunks or supers, see attention.hip)
+  bool attn_super; // one workgroup per super (many sequences) instead of per chunk
   int32_t *row_pos, *row_seq, *seq_len, *seq_n, *dump_slot;
   float* resid;
   uint16_t *normed, *q, *attn, *hidden;
   float *part_acc, *part_ml;
+  float* split_part;   // fp32 partial of a split GEMM on the large-batch path, [m_pad][d_model]
   float2* amax;   // [m_pad][vocab/16] (value, index bits)
   size_t bytes;
 };
@@ -114,6 +114,7 @@ void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, in
 void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hipStream_t st);
 void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const Workspace& ws, hipStream_t st);
 
+int attention_units(bool super_mode, int max_context);
 void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv, int num_seqs, int window,
                       int max_context, const Workspace& ws, hipStream_t st);
 void launch_argmax_merge(const llm42_model* m, int num_seqs, int window, int32_t* out_tokens, const Workspace& ws,

@@ -87,76 +87,80 @@ __global__ void embed_kernel(const uint16_t* __restrict__ table, const int32_t* 
   *(f32x4*)(resid + resid_off(row, feat + 4, d)) = hi;
 }
 
-// RMSNorm over a 16-row block per workgroup of NORM_WAVES waves; fp32 residual
-// stream in, bf16 tile layout (the next GEMM's activation operand) out.
-// Reduction schedule per row (a function of d only):
-//   lane (row, g) of wave w accumulates, in feature order, the squares of features
-//   t*32 + g*8 .. +7 for t = w, w+16, w+32, ...;  the 4 g-lanes of a row are then
-//   added by the (lane ^ 16) and (lane ^ 32) butterflies;  the 16 wave sums are
-//   added in wave order.
-constexpr int NORM_WAVES = 16;
-__global__ __launch_bounds__(NORM_WAVES * 64) void rmsnorm_kernel(const float* __restrict__ x, const uint16_t* __restrict__ gain,
-                                                      uint4* __restrict__ y, int d, float eps) {
-  __shared__ float part[NORM_WAVES][16];
+// RMSNorm, one wave per row (4 rows per workgroup); fp32 residual stream in, bf16
+// tile layout (the next GEMM's activation operand) out.
+// Reduction schedule per row (a function of d only): 64 partial sums p[w][g],
+// w = 0..15, g = 0..3; p[w][g] accumulates, in ascending feature order, the squares
+// of features t*32 + g*8 .. +7 for t = w, w+16, w+32, ...; then per w the four g
+// are added as (p[w][g] + p[w][g^1]) + (p[w][g^2] + p[w][g^3]), and the 16 results
+// are added in ascending w.  Lane w*4+g of the row's wave owns p[w][g].
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const uint16_t* __restrict__ gain,
+                                                      uint16_t* __restrict__ y, int m_pad, int d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= m_pad) return;
+  const int w = lane >> 2, g = lane & 3;
   const int col_tiles = d / 32;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 16 + (lane & 15), g = lane >> 4;
-  uint4* yr = y + (size_t)blockIdx.x * col_tiles * 64 + lane;
+  constexpr int U = 8;                                   // tiles in flight per lane
+  const int full = col_tiles / (16 * U);                 // rounds in which every lane has U tiles
+  const float* xr = x + resid_off(row, 0, d);            // feature f of this row: xr + (f / 4) * 64 + f % 4
+  uint4* yr = (uint4*)(y + pk_off(row, 0, d));           // 8 features from f (f % 8 == 0): yr + (f/32)*64 + ((f%32)/8)*16
   float ss = 0.f;
-  constexpr int U = 8;   // tiles in flight per wave
-  for (int t0 = wave; t0 < col_tiles; t0 += NORM_WAVES * U) {
+  // (no load sits behind a per-load condition: the compiler would serialise such loads)
+  for (int rd = 0; rd < full; ++rd) {
     f32x4 a[U], b[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int t = t0 + u * NORM_WAVES;
-      if (t < col_tiles) {
-        a[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
-        b[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
-      }
+      const int f = ((rd * U + u) * 16 + w) * 32 + g * 8;
+      a[u] = *(const f32x4*)(xr + (f >> 2) * 64);
+      b[u] = *(const f32x4*)(xr + (f >> 2) * 64 + 64);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (t0 + u * NORM_WAVES < col_tiles) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[u][i], a[u][i], ss);
+      for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[u][i], a[u][i], ss);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[u][i], b[u][i], ss);
-      }
+      for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[u][i], b[u][i], ss);
     }
   }
-  ss += __shfl_xor(ss, 16);
-  ss += __shfl_xor(ss, 32);
-  if (lane < 16) part[wave][lane] = ss;
-  __syncthreads();
-  const int r = lane & 15;
-  float total = part[0][r];
+  for (int t = full * U * 16 + w; t < col_tiles; t += 16) {
+    const int f = t * 32 + g * 8;
+    const f32x4 a = *(const f32x4*)(xr + (f >> 2) * 64), b = *(const f32x4*)(xr + (f >> 2) * 64 + 64);
 #pragma unroll
-  for (int w = 1; w < NORM_WAVES; ++w) total += part[w][r];
+    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[i], a[i], ss);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[i], b[i], ss);
+  }
+  ss += __shfl_xor(ss, 1);
+  ss += __shfl_xor(ss, 2);
+  float total = __shfl(ss, 0);
+#pragma unroll
+  for (int ww = 1; ww < 16; ++ww) total += __shfl(ss, ww * 4);
   const float inv = 1.0f / __builtin_sqrtf(total / (float)d + eps);
-  for (int t0 = wave; t0 < col_tiles; t0 += NORM_WAVES * U) {
+  auto emit = [&](int f, const f32x4 a, const f32x4 b, const uint4 gv) {
+    uint4 o;
+    o.x = pack2_bf16(a[0] * inv * bf16_bits_to_f32(gv.x & 0xFFFFu), a[1] * inv * bf16_bits_to_f32(gv.x >> 16));
+    o.y = pack2_bf16(a[2] * inv * bf16_bits_to_f32(gv.y & 0xFFFFu), a[3] * inv * bf16_bits_to_f32(gv.y >> 16));
+    o.z = pack2_bf16(b[0] * inv * bf16_bits_to_f32(gv.z & 0xFFFFu), b[1] * inv * bf16_bits_to_f32(gv.z >> 16));
+    o.w = pack2_bf16(b[2] * inv * bf16_bits_to_f32(gv.w & 0xFFFFu), b[3] * inv * bf16_bits_to_f32(gv.w >> 16));
+    yr[(f >> 5) * 64 + ((f & 31) >> 3) * 16] = o;
+  };
+  for (int rd = 0; rd < full; ++rd) {
     f32x4 a[U], b[U];
     uint4 gv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int t = t0 + u * NORM_WAVES;
-      if (t < col_tiles) {
-        a[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8, d));
-        b[u] = *(const f32x4*)(x + resid_off(row, t * 32 + g * 8 + 4, d));
-        gv[u] = *(const uint4*)(gain + t * 32 + g * 8);
-      }
+      const int f = ((rd * U + u) * 16 + w) * 32 + g * 8;
+      a[u] = *(const f32x4*)(xr + (f >> 2) * 64);
+      b[u] = *(const f32x4*)(xr + (f >> 2) * 64 + 64);
+      gv[u] = *(const uint4*)(gain + f);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int t = t0 + u * NORM_WAVES;
-      if (t < col_tiles) {
-        uint4 o;
-        o.x = pack2_bf16(a[u][0] * inv * bf16_bits_to_f32(gv[u].x & 0xFFFFu), a[u][1] * inv * bf16_bits_to_f32(gv[u].x >> 16));
-        o.y = pack2_bf16(a[u][2] * inv * bf16_bits_to_f32(gv[u].y & 0xFFFFu), a[u][3] * inv * bf16_bits_to_f32(gv[u].y >> 16));
-        o.z = pack2_bf16(b[u][0] * inv * bf16_bits_to_f32(gv[u].z & 0xFFFFu), b[u][1] * inv * bf16_bits_to_f32(gv[u].z >> 16));
-        o.w = pack2_bf16(b[u][2] * inv * bf16_bits_to_f32(gv[u].w & 0xFFFFu), b[u][3] * inv * bf16_bits_to_f32(gv[u].w >> 16));
-        yr[(size_t)t * 64] = o;
-      }
-    }
+    for (int u = 0; u < U; ++u) emit(((rd * U + u) * 16 + w) * 32 + g * 8, a[u], b[u], gv[u]);
+  }
+  for (int t = full * U * 16 + w; t < col_tiles; t += 16) {
+    const int f = t * 32 + g * 8;
+    emit(f, *(const f32x4*)(xr + (f >> 2) * 64), *(const f32x4*)(xr + (f >> 2) * 64 + 64), *(const uint4*)(gain + f));
   }
 }
 
@@ -182,5 +186,5 @@ void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspa
 
 void launch_rmsnorm(const float* x, const uint16_t* gain, uint16_t* y, int m_pad, int d, float eps,
                     hipStream_t st) {
-  rmsnorm_kernel<<<m_pad / 16, NORM_WAVES * 64, 0, st>>>(x, gain, (uint4*)y, d, eps);
+  rmsnorm_kernel<<<(m_pad + 3) / 4, 256, 0, st>>>(x, gain, y, m_pad, d, eps);
 }

@@ -22,9 +22,19 @@ __global__ __launch_bounds__(256) void argmax_merge_kernel(const float2* __restr
   if (row_pos[row] < 0) return;   // dead row: out_tokens stays -1 (whole workgroup leaves)
   float bv = -INFINITY;
   int bi = 0x7FFFFFFF;
-  for (int b = threadIdx.x; b < n_blocks; b += 256) {
-    const float2 p = amax[(size_t)row * n_blocks + b];
-    take_better(bv, bi, p.x, __float_as_int(p.y));
+  const float2* p = amax + (size_t)row * n_blocks;
+  constexpr int U = 8;                                    // partials in flight per thread
+  int b = threadIdx.x;
+  for (; b + (U - 1) * 256 < n_blocks; b += U * 256) {
+    float2 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = p[b + u * 256];
+#pragma unroll
+    for (int u = 0; u < U; ++u) take_better(bv, bi, v[u].x, __float_as_int(v[u].y));
+  }
+  for (; b < n_blocks; b += 256) {
+    const float2 v = p[b];
+    take_better(bv, bi, v.x, __float_as_int(v.y));
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) take_better(bv, bi, __shfl_xor(bv, off), __shfl_xor(bi, off));
