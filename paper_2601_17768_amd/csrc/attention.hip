@@ -79,16 +79,32 @@ __global__ __launch_bounds__(256) void attention_kernel(
   const int col = lane & 15, g = lane >> 4;
   const int unit = blockIdx.x;
   const int s = blockIdx.z / n_kv_heads, kvh = blockIdx.z % n_kv_heads;
-  const int L = seq_len[s], n = seq_n[s];
-  if (L < 0) return;                                         // whole workgroup
   const int k_lo = unit * UNIT;
   const int32_t* bt = block_table + (size_t)s * max_blocks_per_seq;
-
-  int qpos[CB], row[CB];
-  int wmax = -1;
+  // Requested before anything is known about the sequence, so that the three latencies (lengths,
+  // block ids, query operands) overlap: the unit's block-table entries (clamped to the table, not
+  // yet to the sequence) and the query operands of this wave's row blocks.
+  const int first_blk = k_lo >> 4;
+  const int raw0 = bt[min(first_blk + lane, max_blocks_per_seq - 1)];
+  const int raw1 = SUPER ? bt[min(first_blk + 64 + lane, max_blocks_per_seq - 1)] : 0;
+  Frag qf[CB][DK];
+  int row[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     row[cb] = ((blockIdx.y * 4 + wave) * CB + cb) * 16 + col;
+    // row blocks past r_pad (grid padding) read the last real block instead; their rows are dead anyway
+    const int rb = min(row[cb] >> 4, r_pad / 16 - 1);
+    const uint16_t* qb = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)rb * DK * 512;
+#pragma unroll
+    for (int d = 0; d < DK; ++d) qf[cb][d].u = *(const uint4*)(qb + d * 512 + lane * 8);
+  }
+  const int L = seq_len[s], n = seq_n[s];
+  if (L < 0) return;                                         // whole workgroup
+
+  int qpos[CB];
+  int wmax = -1;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
     const int i = row[cb] % window;
     qpos[cb] = (row[cb] < group * window && i < n) ? L + i : -1;
     wmax = max(wmax, qpos[cb]);
@@ -101,22 +117,12 @@ __global__ __launch_bounds__(256) void attention_kernel(
   if (gmax < k_lo) return;                                   // whole workgroup: nobody looks into this unit
   const int k_hi = min(gmax + 1, k_lo + UNIT);               // exclusive; <= L + n
   const int n_stages = (k_hi - k_lo + STAGE - 1) / STAGE;
-  const int first_blk = k_lo >> 4, last_blk = (k_hi - 1) >> 4;
-
-  // physical ids of this unit's blocks, one or two per lane; blocks past the last needed one are
-  // replaced by it (their data is fetched but every key in them is masked)
-  const int ids0 = bt[min(first_blk + lane, last_blk)];
-  const int ids1 = SUPER ? bt[min(first_blk + 64 + lane, last_blk)] : 0;
-
-  Frag qf[CB][DK];
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) {
-    // row blocks past r_pad (grid padding) read the last real block instead; their rows are dead anyway
-    const int rb = min(row[cb] >> 4, r_pad / 16 - 1);
-    const uint16_t* qb = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)rb * DK * 512;
-#pragma unroll
-    for (int d = 0; d < DK; ++d) qf[cb][d].u = *(const uint4*)(qb + d * 512 + lane * 8);
-  }
+  const int last_blk = (k_hi - 1) >> 4;
+  // table entries past the last needed block may hold anything: replace them by the last needed
+  // block's id (its data is fetched in their place, and every key in those positions is masked)
+  const int last_id = __shfl((last_blk - first_blk) < 64 ? raw0 : raw1, (last_blk - first_blk) & 63);
+  const int ids0 = first_blk + lane <= last_blk ? raw0 : last_id;
+  const int ids1 = first_blk + 64 + lane <= last_blk ? raw1 : last_id;
 
   // each wave fetches two of the eight blocks of a stage, straight from global memory into LDS
   // (no staging registers): one instruction moves 1 KiB, lane i's 16 bytes landing at base + 16 i

@@ -22,17 +22,34 @@ struct QkvEpi {
   uint16_t* v_plane;
   int n_q_heads, n_kv_heads, head_dim, group, window, r_pad, max_blocks_per_seq;
 
-  __device__ void operator()(int nb, int lane, int row, const f32x4 acc) const {
-    const int pos = row_pos[row];
+  // What the epilogue needs from memory besides the accumulators; requested when the kernel
+  // starts so that its latency hides behind the weight stream.
+  struct Pre {
+    int pos, s, blk;
+    float2 cs0, cs1;
+  };
+  __device__ Pre pre(int nb, int lane, int row) const {
+    Pre p;
+    p.pos = row_pos[row];
+    p.s = row_seq[row];
+    const int safe = max(p.pos, 0);
+    const int j0 = (nb % (head_dim >> 4)) * 8 + (lane >> 4) * 2;
+    p.cs0 = rope[(size_t)safe * (head_dim >> 1) + j0];
+    p.cs1 = rope[(size_t)safe * (head_dim >> 1) + j0 + 1];
+    p.blk = block_table[(size_t)p.s * max_blocks_per_seq + (safe >> 4)];
+    return p;
+  }
+  __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
+    const int pos = p.pos;
     if (pos < 0) return;
     const int blocks_per_head = head_dim >> 4;
     const int head = nb / blocks_per_head, t = nb % blocks_per_head, g = lane >> 4;
     const int j0 = t * 8 + g * 2;           // features j0, j0+1 and their rotary partners j0 + hd/2, j0+1 + hd/2
     const int half = head_dim >> 1;
-    const int s = row_seq[row];
+    const int s = p.s;
     float lo0 = acc[0], lo1 = acc[1], hi0 = acc[2], hi1 = acc[3];
     if (head < n_q_heads + n_kv_heads) {
-      const float2 cs0 = rope[(size_t)pos * half + j0], cs1 = rope[(size_t)pos * half + j0 + 1];
+      const float2 cs0 = p.cs0, cs1 = p.cs1;
       const float a0 = lo0 * cs0.x - hi0 * cs0.y, b0 = hi0 * cs0.x + lo0 * cs0.y;
       const float a1 = lo1 * cs1.x - hi1 * cs1.y, b1 = hi1 * cs1.x + lo1 * cs1.y;
       lo0 = a0; hi0 = b0; lo1 = a1; hi1 = b1;
@@ -45,7 +62,7 @@ struct QkvEpi {
       *(uint32_t*)(base + pk_off(r, j0 + half, head_dim)) = hi;
       return;
     }
-    const int blk = block_table[(size_t)s * max_blocks_per_seq + (pos >> 4)];
+    const int blk = p.blk;
     const int tok = pos & 15;
     if (head < n_q_heads + n_kv_heads) {
       uint16_t* tile = k_plane + ((size_t)blk * n_kv_heads + (head - n_q_heads)) * 16 * head_dim;
@@ -64,9 +81,14 @@ struct QkvEpi {
 struct ResidualEpi {
   float* resid;   // fp32 residual stream [m_pad][n], updated in place (one lane owns each element)
   int n;
-  __device__ void operator()(int nb, int lane, int row, const f32x4 acc) const {
-    f32x4* p = (f32x4*)(resid + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
-    *p = *p + acc;
+  struct Pre {
+    f32x4 old;
+  };
+  __device__ Pre pre(int nb, int lane, int row) const {
+    return Pre{*(const f32x4*)(resid + resid_off(row, nb * 16 + (lane >> 4) * 4, n))};
+  }
+  __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
+    *(f32x4*)(resid + resid_off(row, nb * 16 + (lane >> 4) * 4, n)) = p.old + acc;
   }
 };
 
@@ -75,7 +97,9 @@ __device__ inline float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
 struct SwigluEpi {
   uint16_t* hidden;  // tile layout [m_pad][ffn_k]
   int ffn_k;
-  __device__ void operator()(int nb, int lane, int row, const f32x4 acc) const {
+  struct Pre {};
+  __device__ Pre pre(int, int, int) const { return Pre{}; }
+  __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre&) const {
     // acc[0], acc[1]: gate of hidden features f, f+1;  acc[2], acc[3]: up of the same features
     const int f = nb * 8 + (lane >> 4) * 2;
     const float h0 = silu_f32(acc[0]) * acc[2], h1 = silu_f32(acc[1]) * acc[3];
@@ -90,10 +114,20 @@ struct LogitsEpi {
   float* out_logits;   // [n_dump][window][vocab] or null
   float2* amax;        // [m_pad][n_blocks]
   int window, vocab, n_blocks;
-  __device__ void operator()(int nb, int lane, int row, const f32x4 acc) const {
+  struct Pre {
+    int pos, s, slot;
+  };
+  __device__ Pre pre(int, int, int row) const {
+    Pre p;
+    p.pos = row_pos[row];
+    p.s = row_seq[row];
+    p.slot = out_logits ? dump_slot[p.s] : -1;
+    return p;
+  }
+  __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
     const int n0 = nb * 16 + (lane >> 4) * 4;
-    if (out_logits && row_pos[row] >= 0) {
-      const int s = row_seq[row], slot = dump_slot[s];
+    if (out_logits && p.pos >= 0) {
+      const int s = p.s, slot = p.slot;
       if (slot >= 0)
         *(f32x4*)(out_logits + ((size_t)slot * window + (row - s * window)) * vocab + n0) = acc;
     }
@@ -158,14 +192,16 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const bf16x8* __restri
   for (int b = 0; b < MB; ++b) {
     const int row = (mb0 + b) * 16 + (lane & 15);
     if (ADD_PARTIAL) acc[b] = acc[b] + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
-    epi(nb, lane, row, acc[b]);
+    epi(nb, lane, row, acc[b], epi.pre(nb, lane, row));
   }
 }
 
 struct StorePartialEpi {
   float* partial;   // [m_pad][n] in the residual-stream layout
   int n;
-  __device__ void operator()(int nb, int lane, int row, const f32x4 acc) const {
+  struct Pre {};
+  __device__ Pre pre(int, int, int) const { return Pre{}; }
+  __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre&) const {
     *(f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n)) = acc;
   }
 };
@@ -196,38 +232,44 @@ __global__ __launch_bounds__(256 * SPLIT) void gemm_coop_kernel(const bf16x8* __
   const bf16x8* xp = x + ((size_t)gw * k_tiles + k_begin) * 64 + lane;   // consumer gw owns token block gw
   const bool consumer = gw < MB;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  bf16x8 wr[CH / 4], xr[CH];
-  // no load below sits behind a per-load condition: the compiler would serialise such loads
-  if (my_rounds > 0) {
+  bf16x8 wa[CH / 4], wb[CH / 4], xr[CH];
+  // Weight tiles are requested two rounds ahead (register sets wa / wb alternate), activation tiles
+  // one round ahead.  No load sits behind a per-load condition: the compiler would serialise them.
+  auto load_w = [&](bf16x8(&dst)[CH / 4], int r) {
+    const bf16x8* p = wp + (size_t)r * CH * 64;
 #pragma unroll
-    for (int i = 0; i < CH / 4; ++i) wr[i] = __builtin_nontemporal_load(wp + (size_t)(i * 4 + gw) * 64);
-    if (consumer) {
+    for (int i = 0; i < CH / 4; ++i) dst[i] = __builtin_nontemporal_load(p + (size_t)(i * 4 + gw) * 64);
+  };
+  auto load_x = [&](int r) {
+    const bf16x8* p = xp + (size_t)r * CH * 64;
 #pragma unroll
-      for (int j = 0; j < CH; ++j) xr[j] = xp[(size_t)j * 64];
-    }
-  }
-  for (int r = 0; r < rounds; ++r) {
-    const bool live = r < my_rounds, more = r + 1 < my_rounds;
+    for (int j = 0; j < CH; ++j) xr[j] = p[(size_t)j * 64];
+  };
+  auto round = [&](bf16x8(&cur)[CH / 4], int r) {   // consume round r (held in cur), refill cur with round r + 2
+    const bool live = r < my_rounds;
     if (live) {
 #pragma unroll
-      for (int i = 0; i < CH / 4; ++i) wlds[grp][(i * 4 + gw) * 64 + lane] = wr[i];
+      for (int i = 0; i < CH / 4; ++i) wlds[grp][(i * 4 + gw) * 64 + lane] = cur[i];
     }
     __syncthreads();
-    const bf16x8* wn = wp + (size_t)(r + 1) * CH * 64;
-    const bf16x8* xn = xp + (size_t)(r + 1) * CH * 64;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < CH / 4; ++i) wr[i] = __builtin_nontemporal_load(wn + (size_t)(i * 4 + gw) * 64);
-    }
+    if (r + 2 < my_rounds) load_w(cur, r + 2);
     if (consumer && live) {
 #pragma unroll
       for (int j = 0; j < CH; ++j) acc = mfma16(wlds[grp][j * 64 + lane], xr[j], acc);
-      if (more) {
-#pragma unroll
-        for (int j = 0; j < CH; ++j) xr[j] = xn[(size_t)j * 64];
-      }
+      if (r + 1 < my_rounds) load_x(r + 1);
     }
     __syncthreads();
+  };
+  if (my_rounds > 0) {
+    load_w(wa, 0);
+    if (consumer) load_x(0);
+  }
+  if (my_rounds > 1) load_w(wb, 1);
+  typename Epi::Pre pre{};
+  if (consumer && grp == 0) pre = epi.pre(nb, lane, gw * 16 + (lane & 15));
+  for (int r = 0; r < rounds; r += 2) {
+    round(wa, r);
+    if (r + 1 < rounds) round(wb, r + 1);
   }
   if (consumer) {   // tail of fewer than CH tiles (model dimensions that are no multiple of 1024): tile by tile
     for (int kt = my_rounds * CH; kt < k_count; ++kt) acc = mfma16(wp[(size_t)kt * 64], xp[(size_t)kt * 64], acc);
@@ -237,7 +279,7 @@ __global__ __launch_bounds__(256 * SPLIT) void gemm_coop_kernel(const bf16x8* __
     __syncthreads();
     if (consumer && grp == 0) acc = acc + merge[gw][lane];
   }
-  if (consumer && grp == 0) epi(nb, lane, gw * 16 + (lane & 15), acc);
+  if (consumer && grp == 0) epi(nb, lane, gw * 16 + (lane & 15), acc, pre);
 }
 
 // Small-batch kernel for wide outputs (at most 64 tokens): 8 waves per workgroup, every wave owns
@@ -245,15 +287,17 @@ __global__ __launch_bounds__(256 * SPLIT) void gemm_coop_kernel(const bf16x8* __
 // round (CH k-tiles) ahead of their use.  The activation tiles, which all 8 waves need, are fetched
 // once per workgroup and shared through LDS (double buffered), which cuts the L2 traffic for
 // activations by 8.  Accumulation order per output element: as stated above.
-template <int MB, class Epi>
+// NBW (7 or 8) of the 8 waves own a feature block; with NBW = 7 the eighth wave only helps fetching
+// activations (this makes the grid of the 8B gate/up GEMM exactly one workgroup per CU).
+template <int MB, int NBW, class Epi>
 __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                           int n_blocks, int k_tiles, Epi epi) {
   constexpr int CH = 16, NW = 8;
   constexpr int XT = MB * CH / NW;                   // activation tiles each wave fetches per round
   __shared__ bf16x8 xlds[2][MB * CH * 64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nb = min(blockIdx.x * NW + wave, n_blocks - 1);   // surplus waves redo the last block, discarded below
-  const bool owner = blockIdx.x * NW + wave < n_blocks;
+  const int nb = min(blockIdx.x * NBW + wave, n_blocks - 1);  // surplus waves redo a block, discarded below
+  const bool owner = wave < NBW && blockIdx.x * NBW + wave < n_blocks;
   const bf16x8* wp = w + (size_t)nb * k_tiles * 64 + lane;
   const bf16x8* xp = x + lane;
   f32x4 acc[MB];
@@ -288,8 +332,11 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   if (rounds > 0) {
     load_w(wa, 0);
     load_x(0);
-    store_x(0);
   }
+  typename Epi::Pre pre[MB];
+#pragma unroll
+  for (int b = 0; b < MB; ++b) pre[b] = epi.pre(nb, lane, b * 16 + (lane & 15));
+  if (rounds > 0) store_x(0);
   __syncthreads();
   for (int r = 0; r < rounds; r += 2) {
     // even round: consume wa / buffer 0 while wb / buffer 1 are in flight
@@ -316,7 +363,7 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   }
   if (owner) {
 #pragma unroll
-    for (int b = 0; b < MB; ++b) epi(nb, lane, b * 16 + (lane & 15), acc[b]);
+    for (int b = 0; b < MB; ++b) epi(nb, lane, b * 16 + (lane & 15), acc[b], pre[b]);
   }
 }
 
@@ -332,10 +379,19 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
   const bf16x8* xp = (const bf16x8*)x;
   if (m_pad <= 64) {
     if (wide && SPLIT == 1) {
-      const unsigned gx = (unsigned)((n_blocks + 7) / 8);
-      if (m_pad == 16) gemm_xshare_kernel<1, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
-      else if (m_pad == 32) gemm_xshare_kernel<2, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
-      else gemm_xshare_kernel<4, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+      // 7 or 8 feature blocks per workgroup: whichever needs less (rounds of 256 workgroups) x (blocks each)
+      const int g8 = (n_blocks + 7) / 8, g7 = (n_blocks + 6) / 7;
+      const bool seven = ((g7 + 255) / 256) * 7 < ((g8 + 255) / 256) * 8;
+      const unsigned gx = (unsigned)(seven ? g7 : g8);
+      if (seven) {
+        if (m_pad == 16) gemm_xshare_kernel<1, 7, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+        else if (m_pad == 32) gemm_xshare_kernel<2, 7, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+        else gemm_xshare_kernel<4, 7, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+      } else {
+        if (m_pad == 16) gemm_xshare_kernel<1, 8, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+        else if (m_pad == 32) gemm_xshare_kernel<2, 8, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+        else gemm_xshare_kernel<4, 8, Epi><<<gx, 512, 0, st>>>(wp, xp, n_blocks, k_tiles, epi);
+      }
     } else {
       if (m_pad == 16) gemm_coop_kernel<1, SPLIT, Epi><<<n_blocks, 256 * SPLIT, 0, st>>>(wp, xp, k_tiles, epi);
       else if (m_pad == 32) gemm_coop_kernel<2, SPLIT, Epi><<<n_blocks, 256 * SPLIT, 0, st>>>(wp, xp, k_tiles, epi);

@@ -87,6 +87,27 @@ __global__ void embed_kernel(const uint16_t* __restrict__ table, const int32_t* 
   *(f32x4*)(resid + resid_off(row, feat + 4, d)) = hi;
 }
 
+// Sum of the 64 per-lane partial sums of squares of a row (lane w*4+g owns p[w][g]) in the fixed
+// order stated at rmsnorm_kernel, and the row's 1 / sqrt(mean square + eps).
+__device__ inline float row_inv_rms(float ss, int d, float eps) {
+  ss += __shfl_xor(ss, 1);
+  ss += __shfl_xor(ss, 2);
+  float total = __shfl(ss, 0);
+#pragma unroll
+  for (int ww = 1; ww < 16; ++ww) total += __shfl(ss, ww * 4);
+  return 1.0f / __builtin_sqrtf(total / (float)d + eps);
+}
+
+// y[f .. f+7] = bf16(x * inv * gain), written into the tile layout; yr points at the row's feature 0.
+__device__ inline void emit_normed(uint4* yr, int f, const f32x4 a, const f32x4 b, const uint4 gv, float inv) {
+  uint4 o;
+  o.x = pack2_bf16(a[0] * inv * bf16_bits_to_f32(gv.x & 0xFFFFu), a[1] * inv * bf16_bits_to_f32(gv.x >> 16));
+  o.y = pack2_bf16(a[2] * inv * bf16_bits_to_f32(gv.y & 0xFFFFu), a[3] * inv * bf16_bits_to_f32(gv.y >> 16));
+  o.z = pack2_bf16(b[0] * inv * bf16_bits_to_f32(gv.z & 0xFFFFu), b[1] * inv * bf16_bits_to_f32(gv.z >> 16));
+  o.w = pack2_bf16(b[2] * inv * bf16_bits_to_f32(gv.w & 0xFFFFu), b[3] * inv * bf16_bits_to_f32(gv.w >> 16));
+  yr[(f >> 5) * 64 + ((f & 31) >> 3) * 16] = o;
+}
+
 // RMSNorm, one wave per row (4 rows per workgroup); fp32 residual stream in, bf16
 // tile layout (the next GEMM's activation operand) out.
 // Reduction schedule per row (a function of d only): 64 partial sums p[w][g],
@@ -107,6 +128,29 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   uint4* yr = (uint4*)(y + pk_off(row, 0, d));           // 8 features from f (f % 8 == 0): yr + (f/32)*64 + ((f%32)/8)*16
   float ss = 0.f;
   // (no load sits behind a per-load condition: the compiler would serialise such loads)
+  if (full == 1 && col_tiles == 16 * U) {
+    // d = 4096: the lane's whole share of the row (and of the gains) stays in registers
+    f32x4 a[U], b[U];
+    uint4 gv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int f = (u * 16 + w) * 32 + g * 8;
+      a[u] = *(const f32x4*)(xr + (f >> 2) * 64);
+      b[u] = *(const f32x4*)(xr + (f >> 2) * 64 + 64);
+      gv[u] = *(const uint4*)(gain + f);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[u][i], a[u][i], ss);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[u][i], b[u][i], ss);
+    }
+    const float inv = row_inv_rms(ss, d, eps);
+#pragma unroll
+    for (int u = 0; u < U; ++u) emit_normed(yr, (u * 16 + w) * 32 + g * 8, a[u], b[u], gv[u], inv);
+    return;
+  }
   for (int rd = 0; rd < full; ++rd) {
     f32x4 a[U], b[U];
 #pragma unroll
@@ -131,20 +175,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 #pragma unroll
     for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[i], b[i], ss);
   }
-  ss += __shfl_xor(ss, 1);
-  ss += __shfl_xor(ss, 2);
-  float total = __shfl(ss, 0);
-#pragma unroll
-  for (int ww = 1; ww < 16; ++ww) total += __shfl(ss, ww * 4);
-  const float inv = 1.0f / __builtin_sqrtf(total / (float)d + eps);
-  auto emit = [&](int f, const f32x4 a, const f32x4 b, const uint4 gv) {
-    uint4 o;
-    o.x = pack2_bf16(a[0] * inv * bf16_bits_to_f32(gv.x & 0xFFFFu), a[1] * inv * bf16_bits_to_f32(gv.x >> 16));
-    o.y = pack2_bf16(a[2] * inv * bf16_bits_to_f32(gv.y & 0xFFFFu), a[3] * inv * bf16_bits_to_f32(gv.y >> 16));
-    o.z = pack2_bf16(b[0] * inv * bf16_bits_to_f32(gv.z & 0xFFFFu), b[1] * inv * bf16_bits_to_f32(gv.z >> 16));
-    o.w = pack2_bf16(b[2] * inv * bf16_bits_to_f32(gv.w & 0xFFFFu), b[3] * inv * bf16_bits_to_f32(gv.w >> 16));
-    yr[(f >> 5) * 64 + ((f & 31) >> 3) * 16] = o;
-  };
+  const float inv = row_inv_rms(ss, d, eps);
   for (int rd = 0; rd < full; ++rd) {
     f32x4 a[U], b[U];
     uint4 gv[U];
@@ -156,11 +187,12 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
       gv[u] = *(const uint4*)(gain + f);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) emit(((rd * U + u) * 16 + w) * 32 + g * 8, a[u], b[u], gv[u]);
+    for (int u = 0; u < U; ++u) emit_normed(yr, ((rd * U + u) * 16 + w) * 32 + g * 8, a[u], b[u], gv[u], inv);
   }
   for (int t = full * U * 16 + w; t < col_tiles; t += 16) {
     const int f = t * 32 + g * 8;
-    emit(f, *(const f32x4*)(xr + (f >> 2) * 64), *(const f32x4*)(xr + (f >> 2) * 64 + 64), *(const uint4*)(gain + f));
+    emit_normed(yr, f, *(const f32x4*)(xr + (f >> 2) * 64), *(const f32x4*)(xr + (f >> 2) * 64 + 64),
+                *(const uint4*)(gain + f), inv);
   }
 }
 

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from helpers import orc, wl
-from gpu_helpers import Scenario, VerifierSession, assert_logits_close, oracle_kv_to_gpu, gpu_kv_tokens, assert_tokens_match_where_decidable, ABS_TOL
+from gpu_helpers import Scenario, VerifierSession, assert_logits_within_noise, oracle_kv_to_gpu, gpu_kv_tokens, assert_tokens_match_where_decidable, ABS_TOL
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -41,10 +41,21 @@ def test_mid_shape_against_checker():
     torch.cuda.synchronize()
     assert status.tolist() == [0, 0, 0]
     o_tokens, o_logits = sc.oracle_verify()
+    # the checker's own sensitivity to accumulation order on these inputs: float32 instead of float64
+    w32 = as_dtype(w, torch.float32)
+    noise = []
+    for s in range(3):
+        L = int(sc.lens[s])
+        kv32 = orc.OracleKV(sc.cfg, L + window)
+        kv32.k[:, :L] = sc.okv[s].k[:, :L]
+        kv32.v[:, :L] = sc.okv[s].v[:, :L]
+        lg32 = orc.forward_window(sc.cfg, w32, kv32, L, sc.candidates[s], acc_dtype=torch.float32).double()
+        noise.append((lg32 - o_logits[s]).abs())
+    noise = torch.cat(noise)
+    noise_rms, noise_max = float((noise * noise).mean().sqrt()), float(noise.max())
     exempt = 0
     for s in range(3):
-        err, rms = assert_logits_close(logits[s], o_logits[s], f"seq {s}", strict_abs=False)
-        print(f"mid shape seq {s}: logit error max {err:.3e} rms {rms:.3e}, scale {float(o_logits[s].abs().max()):.2f}")
+        err, rms = assert_logits_within_noise(logits[s], o_logits[s], noise_rms, noise_max, f"mid shape seq {s}")
         margin = orc.top2_margin(o_logits[s])
         seq_exempt = assert_tokens_match_where_decidable(out[s].cpu(), logits[s], o_tokens[s], o_logits[s], f"seq {s}")
         exempt += seq_exempt
