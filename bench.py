@@ -27,6 +27,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per gate/up launch from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
+# profiles/gate_up_gemm_c2_pmc.md (counter x factor from a plain kernel of known traffic); valid for
+# the c2 workload and the kernel named in "roofline"
+PMC_TRAFFIC_BYTES = {"c2": 115744.9 * 1024 * (262144.0 / 131090.5) + 896.0 * 1024}
 WORKLOADS = {
     # name: (num_seqs, window, replacement rate, description)
     "c2": (1, 32, 0.02, "llama-3.1-8B shape random-init, 1 sequence, 512-token prompt, window 32, 2% replaced"),
@@ -88,6 +92,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step kernel by kernel instead of replaying a HIP graph")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain elementwise kernel of known traffic (reads 256 MiB, writes 256 MiB) so "
+                         "that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
     ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalid as a result)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -119,6 +126,12 @@ def main():
     torch.cuda.synchronize()
     log(f"prefill + candidates ready after {time.time() - t0:.1f}s")
 
+    if args.pmc_calibration:
+        src = torch.ones(64 << 20, dtype=torch.int32, device=dev)       # 256 MiB
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)                                      # one kernel: 256 MiB read, 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
     max_context = prompt_len + window
     ws = sess.workspace(num_seqs, window, max_context)
     out = torch.empty((num_seqs, window), dtype=torch.int32, device=dev)
@@ -177,9 +190,10 @@ def main():
     m_pad = 16 if rows <= 16 else 32 if rows <= 32 else (rows + 63) // 64 * 64
     gu_bytes = 2 * shape.d_model * shape.d_ffn * 2 + m_pad * shape.d_model * 2 + m_pad * shape.d_ffn * 2
     achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "gate_up gemm (gemm_stream_kernel, SwiGLU epilogue)",
+    roofline = {"bound": "hbm", "kernel": "gate/up GEMM: gemm_xshare_kernel<2, 7, SwigluEpi>",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": round(PMC_TRAFFIC_BYTES[args.workload]) if args.layers is None else None,
                 "bytes_per_launch": gu_bytes, "avg_launch_ms": round(gu_ms, 5), "launches_timed": len(launches)}
     # whole-pass view: weights streamed once per step
     weight_gbs = shape.gemm_params * 2 / (ms_per_step * 1e-3) / 1e9

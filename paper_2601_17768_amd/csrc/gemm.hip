@@ -296,8 +296,8 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   constexpr int XT = MB * CH / NW;                   // activation tiles each wave fetches per round
   __shared__ bf16x8 xlds[2][MB * CH * 64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nb = min(blockIdx.x * NBW + wave, n_blocks - 1);  // surplus waves redo a block, discarded below
-  const bool owner = wave < NBW && blockIdx.x * NBW + wave < n_blocks;
+  const bool owner = wave < NBW && blockIdx.x * NBW + wave < n_blocks;   // other waves only fetch activations
+  const int nb = owner ? blockIdx.x * NBW + wave : 0;
   const bf16x8* wp = w + (size_t)nb * k_tiles * 64 + lane;
   const bf16x8* xp = x + lane;
   f32x4 acc[MB];
@@ -330,33 +330,35 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   };
 
   if (rounds > 0) {
-    load_w(wa, 0);
+    if (owner) load_w(wa, 0);
     load_x(0);
   }
   typename Epi::Pre pre[MB];
+  if (owner) {
 #pragma unroll
-  for (int b = 0; b < MB; ++b) pre[b] = epi.pre(nb, lane, b * 16 + (lane & 15));
+    for (int b = 0; b < MB; ++b) pre[b] = epi.pre(nb, lane, b * 16 + (lane & 15));
+  }
   if (rounds > 0) store_x(0);
   __syncthreads();
   for (int r = 0; r < rounds; r += 2) {
     // even round: consume wa / buffer 0 while wb / buffer 1 are in flight
     if (r + 1 < rounds) {
-      load_w(wb, r + 1);
+      if (owner) load_w(wb, r + 1);
       load_x(r + 1);
     }
-    compute(wa, 0);
+    if (owner) compute(wa, 0);
     if (r + 1 < rounds) store_x(1);
     __syncthreads();
     if (r + 1 >= rounds) break;
     if (r + 2 < rounds) {
-      load_w(wa, r + 2);
+      if (owner) load_w(wa, r + 2);
       load_x(r + 2);
     }
-    compute(wb, 1);
+    if (owner) compute(wb, 1);
     if (r + 2 < rounds) store_x(0);
     __syncthreads();
   }
-  for (int kt = rounds * CH; kt < k_tiles; ++kt) {   // tail of fewer than CH tiles: tile by tile
+  for (int kt = rounds * CH; owner && kt < k_tiles; ++kt) {   // tail of fewer than CH tiles: tile by tile
     const bf16x8 a = wp[(size_t)kt * 64];
 #pragma unroll
     for (int b = 0; b < MB; ++b) acc[b] = mfma16(a, xp[((size_t)b * k_tiles + kt) * 64], acc[b]);
