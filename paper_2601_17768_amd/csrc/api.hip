@@ -79,7 +79,8 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   Workspace ws;
   memset(&ws, 0, sizeof ws);
   ws.m_rows = num_seqs * window;
-  ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : pad_to(ws.m_rows, 64);
+  ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : ws.m_rows <= 64 ? 64
+             : ws.m_rows <= 512 ? pad_to(ws.m_rows, 128) : pad_to(ws.m_rows, 256);
   ws.r_pad = pad_to(m->group * window, 16);
   // attention work split: per chunk while the grid would otherwise be small, per super beyond that
   const int col_blocks = ws.r_pad / 16, cb_groups = (col_blocks + (col_blocks >= 8 ? 8 : 4) - 1) / (col_blocks >= 8 ? 8 : 4);

@@ -369,6 +369,120 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   }
 }
 
+// Large-batch kernel (more than 64 tokens): MFMA-bound, LDS-tiled.  A workgroup of 4 waves (2 x 2)
+// owns a tile of 32*WB features x 32*WB tokens (WB = 8: 256 x 256, WB = 4: 128 x 128); each wave owns
+// WB x WB MFMA blocks (WB*WB*4 accumulator registers).  Per stage of KS = 2 k-tiles the four waves
+// copy the tile's 2*TB*KS operand tiles (1 KiB each, already in MFMA operand order) from global
+// memory to LDS through registers - the loads of stage s+1 are issued before stage s is computed
+// and parked after it, one barrier per stage, LDS double buffered - and every wave reads its WB
+// weight operands and WB activation operands per k-tile with conflict-free 16-byte LDS reads.
+// Workgroups are numbered so that the workgroups that land on one XCD (id mod 8) walk through
+// consecutive token tiles of the same feature tile: the weight tile is then fetched from HBM once
+// per XCD and served from that XCD's L2 to the other token tiles.
+// Accumulation order per output element: k ascending inside [k_begin, k_begin + k_count), exactly
+// as in the small-batch kernels; with ADD_PARTIAL the other half's fp32 partial is added at the end.
+template <int WB, bool ADD_PARTIAL, class Epi>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
+                                                         int n_blocks, int k_tiles, int k_begin, int k_count,
+                                                         const float* __restrict__ partial, int n, int tiles_n,
+                                                         int tiles_m, Epi epi) {
+  constexpr int TB = 2 * WB;                 // 16-row blocks per tile side
+  constexpr int KS = 2;                      // k-tiles per stage
+  constexpr int ST = 2 * TB * KS;            // operand tiles per stage (weights then activations)
+  constexpr int PW = ST / 4;                 // operand tiles each wave copies per stage
+  __shared__ bf16x8 lds[2][ST * 64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wn = wave >> 1, wm = wave & 1;
+  // XCD-aware numbering: XCD (id % 8) gets a contiguous range of tiles, token tiles fastest
+  const int total = tiles_n * tiles_m, per_xcd = (total + 7) / 8;
+  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (t >= total || (blockIdx.x >> 3) >= per_xcd) return;
+  const int n0 = (t / tiles_m) * TB, m0 = (t % tiles_m) * TB;   // first feature / token block of the tile
+
+  // source of the PW operand tiles this wave copies in every stage (k-tile added per stage)
+  const bf16x8* src[PW];
+  int kk_of[PW];
+#pragma unroll
+  for (int i = 0; i < PW; ++i) {
+    const int q = wave * PW + i;                       // 0 .. ST-1
+    const bool is_w = q < TB * KS;
+    const int blk = (is_w ? q : q - TB * KS) / KS;
+    kk_of[i] = q % KS;
+    const int gb = is_w ? min(n0 + blk, n_blocks - 1) : m0 + blk;   // feature blocks past the matrix re-read the last one
+    src[i] = (is_w ? w : x) + ((size_t)gb * k_tiles + k_begin) * 64 + lane;
+  }
+  f32x4 acc[WB][WB];
+#pragma unroll
+  for (int i = 0; i < WB; ++i)
+#pragma unroll
+    for (int j = 0; j < WB; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int stages = (k_count + KS - 1) / KS;
+  bf16x8 stg[PW];   // (a native vector type: arrays of HIP_vector_type structs end up in scratch)
+  auto fetch = [&](int s) {      // k-tiles past the range re-read the last one (never used)
+#pragma unroll
+    for (int i = 0; i < PW; ++i) stg[i] = src[i][(size_t)min(s * KS + kk_of[i], k_count - 1) * 64];
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PW; ++i) lds[buf][(wave * PW + i) * 64 + lane] = stg[i];
+  };
+  fetch(0);
+  park(0);
+  __syncthreads();
+  for (int s = 0; s < stages; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < stages) fetch(s + 1);
+    const int kmax = min(KS, k_count - s * KS);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      if (kk < kmax) {
+        bf16x8 a[WB];
+#pragma unroll
+        for (int i = 0; i < WB; ++i) a[i] = lds[buf][((wn * WB + i) * KS + kk) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < WB; ++j) {
+          const bf16x8 b = lds[buf][((TB + wm * WB + j) * KS + kk) * 64 + lane];
+#pragma unroll
+          for (int i = 0; i < WB; ++i) acc[i][j] = mfma16(a[i], b, acc[i][j]);
+        }
+      }
+    }
+    if (s + 1 < stages) park(buf ^ 1);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < WB; ++i) {
+    const int nb = n0 + wn * WB + i;
+    if (nb >= n_blocks) continue;
+#pragma unroll
+    for (int j = 0; j < WB; ++j) {
+      const int row = (m0 + wm * WB + j) * 16 + (lane & 15);
+      f32x4 v = acc[i][j];
+      if (ADD_PARTIAL) v = v + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
+      epi(nb, lane, row, v, epi.pre(nb, lane, row));
+    }
+  }
+}
+
+template <int WB, int SPLIT, class Epi>
+void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles, int n, const Workspace& ws,
+                  const Epi& epi, hipStream_t st) {
+  const int tb = 2 * WB, tiles_n = (n_blocks + tb - 1) / tb, tiles_m = ws.m_pad / (16 * tb);
+  const unsigned grid = 8u * (unsigned)((tiles_n * tiles_m + 7) / 8);
+  if (SPLIT == 1) {
+    gemm_tiled_kernel<WB, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr, n, tiles_n,
+                                                            tiles_m, epi);
+  } else {
+    const int h = split_point(k_tiles);
+    StorePartialEpi pe{ws.split_part, n};
+    gemm_tiled_kernel<WB, false, StorePartialEpi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, h, k_tiles - h,
+                                                                        nullptr, n, tiles_n, tiles_m, pe);
+    gemm_tiled_kernel<WB, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part, n, tiles_n,
+                                                           tiles_m, epi);
+  }
+}
+
 enum GemmKind { GEMM_QKV = 0, GEMM_RESIDUAL = 1, GEMM_GATE_UP = 2, GEMM_LOGITS = 3 };
 // The split of each GEMM type (part of the reduction schedule, see above).
 constexpr int kSplit[4] = {1, 2, 1, 1};
@@ -401,17 +515,9 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
     }
     return;
   }
-  // m_pad is a multiple of 64
-  const dim3 grid((unsigned)((n_blocks + 3) / 4), m_pad / 64);
-  if (SPLIT == 1) {
-    gemm_stream_kernel<4, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr, n, epi);
-  } else {
-    const int h = split_point(k_tiles);
-    StorePartialEpi pe{ws.split_part, n};
-    gemm_stream_kernel<4, false, StorePartialEpi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, h, k_tiles - h,
-                                                                        nullptr, n, pe);
-    gemm_stream_kernel<4, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part, n, epi);
-  }
+  // more than 64 tokens: m_pad is a multiple of 128 (up to 512 rows) or of 256 (beyond)
+  if (m_pad >= 512 && m_pad % 256 == 0) launch_tiled<8, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  else launch_tiled<4, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
 }
 
 }  // namespace
