@@ -31,9 +31,17 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 # profiles/gate_up_gemm_c2_pmc.md (counter x factor from a plain kernel of known traffic); valid for
 # the c2 workload and the kernel named in "roofline"
 PMC_TRAFFIC_BYTES = {"c2": 115744.9 * 1024 * (262144.0 / 131090.5) + 896.0 * 1024}
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 WORKLOADS = {
     # name: (num_seqs, window, replacement rate, description)
     "c2": (1, 32, 0.02, "llama-3.1-8B shape random-init, 1 sequence, 512-token prompt, window 32, 2% replaced"),
+    # large-batch configurations (not the headline metric): contexts' KV is seeded noise instead of a prefill,
+    # candidates are random ids (every pass commits 1 token per sequence); the verifier's work does not depend
+    # on either
+    "c3": (32, 64, 0.01, "llama-3.1-8B shape, 32 sequences, contexts lognormal(6.0,1.0)+lognormal(5.3,0.9) clipped "
+                         "to [17, 6144], block 16, window 64; KV = seeded noise, candidates random"),
+    "c5": (128, 32, 0.01, "llama-3.1-8B shape, 128 sequences, contexts uniform 1024-8192, window 32; KV = seeded "
+                          "noise, candidates random"),
 }
 
 
@@ -112,27 +120,33 @@ def main():
     t0 = time.time()
     weights = wl.make_weights(shape, seed=seed)
     log(f"weights generated in {time.time() - t0:.1f}s")
-    sess = VerifierSession(shape, weights, max_position=prompt_len + 2 * window, device="cuda:0")
+    rng = wl.rng_for(seed, 2, 1000)
+    if args.workload == "c2":
+        contexts = np.full(num_seqs, prompt_len, dtype=np.int32)
+    elif args.workload == "c3":
+        contexts = (wl.lognormal_lengths(rng, num_seqs, 6.0, 1.0, 16, 4096) +
+                    wl.lognormal_lengths(rng, num_seqs, 5.3, 0.9, 1, 2048)).astype(np.int32)
+    else:
+        contexts = wl.uniform_lengths(rng, num_seqs, 1024, 8192)
+    max_context = int(contexts.max()) + window
+    sess = VerifierSession(shape, weights, max_position=max_context + window, device="cuda:0")
     log(f"model on device after {time.time() - t0:.1f}s; {B.llm42_schedule_info()}")
     dev = sess.device
-    prompts = [wl.random_tokens(wl.rng_for(seed, 2, s), prompt_len, shape.vocab) for s in range(num_seqs)]
-    rng = wl.rng_for(seed, 2, 1000)
-    table, num_blocks = wl.make_block_table(rng, [prompt_len + window] * num_seqs, 16, spare_blocks=8)
+    table, num_blocks = wl.make_block_table(rng, contexts + window, 16, spare_blocks=8)
     bt = torch.as_tensor(table, device=dev)
     kv = sess.kv_cache(num_blocks)
-    first = sess.prefill(kv, bt, prompts, window=window)
-    seq_lens0 = torch.full((num_seqs,), prompt_len, dtype=torch.int32, device=dev)
-    cand = build_candidates(sess, kv, bt, seq_lens0, first, window, rate, shape, rng)
+    seq_lens0 = torch.as_tensor(contexts, device=dev)
+    if args.workload == "c2":
+        prompts = [wl.random_tokens(wl.rng_for(seed, 2, s), prompt_len, shape.vocab) for s in range(num_seqs)]
+        first = sess.prefill(kv, bt, prompts, window=window)
+        cand = build_candidates(sess, kv, bt, seq_lens0, first, window, rate, shape, rng)
+    else:
+        kv.normal_(generator=torch.Generator(device=dev).manual_seed(seed))
+        cand = torch.as_tensor(wl.random_tokens(rng, num_seqs * window, shape.vocab).reshape(num_seqs, window),
+                               device=dev)
     torch.cuda.synchronize()
-    log(f"prefill + candidates ready after {time.time() - t0:.1f}s")
+    log(f"KV + candidates ready after {time.time() - t0:.1f}s; {int(contexts.sum())} context tokens")
 
-    if args.pmc_calibration:
-        src = torch.ones(64 << 20, dtype=torch.int32, device=dev)       # 256 MiB
-        dst = torch.empty_like(src)
-        torch.add(src, 1, out=dst)                                      # one kernel: 256 MiB read, 256 MiB written
-        torch.cuda.synchronize()
-        del src, dst
-    max_context = prompt_len + window
     ws = sess.workspace(num_seqs, window, max_context)
     out = torch.empty((num_seqs, window), dtype=torch.int32, device=dev)
     counts = torch.empty(num_seqs, dtype=torch.int32, device=dev)
@@ -184,26 +198,36 @@ def main():
     value = rows * args.steps / dt
     committed = int(counts.sum())
 
-    # roofline of the gate/up GEMM: algorithmic bytes per launch = packed gate+up weights, read once,
-    # + the activation operand in + the SwiGLU output out
+    # roofline of the gate/up GEMM, the largest kernel of the pass.  Few rows: HBM bound, algorithmic bytes
+    # per launch = packed gate+up weights, read once, + the activation operand in + the SwiGLU output out.
+    # Many rows: MFMA bound, algorithmic flops per launch = 2 * rows * d_model * 2 d_ffn.
     gu_ms = float(np.mean([ms for _, ms in launches]))
-    m_pad = 16 if rows <= 16 else 32 if rows <= 32 else (rows + 63) // 64 * 64
-    gu_bytes = 2 * shape.d_model * shape.d_ffn * 2 + m_pad * shape.d_model * 2 + m_pad * shape.d_ffn * 2
-    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "gate/up GEMM: gemm_xshare_kernel<2, 7, SwigluEpi>",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": round(PMC_TRAFFIC_BYTES[args.workload]) if args.layers is None else None,
-                "bytes_per_launch": gu_bytes, "avg_launch_ms": round(gu_ms, 5), "launches_timed": len(launches)}
+    m_pad = 16 if rows <= 16 else 32 if rows <= 32 else 64 if rows <= 64 else \
+        (rows + 127) // 128 * 128 if rows <= 512 else (rows + 255) // 256 * 256
+    if rows <= 64:
+        gu_bytes = 2 * shape.d_model * shape.d_ffn * 2 + m_pad * shape.d_model * 2 + m_pad * shape.d_ffn * 2
+        achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gate/up GEMM: gemm_xshare_kernel<2, 7, SwigluEpi>",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": round(PMC_TRAFFIC_BYTES[args.workload]) if args.layers is None else None,
+                    "bytes_per_launch": gu_bytes, "avg_launch_ms": round(gu_ms, 5), "launches_timed": len(launches)}
+    else:
+        gu_flops = 2.0 * rows * shape.d_model * 2 * shape.d_ffn
+        achieved = gu_flops / (gu_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gate/up GEMM: gemm_tiled_kernel<8, false, SwigluEpi>",
+                    "achieved": round(achieved, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                    "flops_per_launch": gu_flops, "avg_launch_ms": round(gu_ms, 5), "launches_timed": len(launches)}
     # whole-pass view: weights streamed once per step
     weight_gbs = shape.gemm_params * 2 / (ms_per_step * 1e-3) / 1e9
 
     # per-class breakdown of one more (untimed) step, for the log
-    B.llm42_profile_enable(None, 16 * shape.n_layers)
+    B.llm42_profile_enable(None, 32 * shape.n_layers)
     step()
     torch.cuda.synchronize()
     per_class = {}
-    for name, ms in B.llm42_profile_collect(16 * shape.n_layers):
+    for name, ms in B.llm42_profile_collect(32 * shape.n_layers):
         per_class[name] = per_class.get(name, 0.0) + ms
     log("kernel classes, ms per step: " + ", ".join(f"{k} {v:.3f}" for k, v in per_class.items()) +
         f"; sum {sum(per_class.values()):.3f}")
@@ -213,17 +237,20 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "num_seqs": num_seqs, "window": window,
-                   "context": prompt_len, "rows_per_step": rows, "n_layers": shape.n_layers,
+                   "context_tokens_total": int(contexts.sum()), "max_context": max_context, "rows_per_step": rows, "n_layers": shape.n_layers,
                    "committed_tokens_per_step": committed},
         "roofline": roofline,
         "pass_weight_stream_GBps": round(weight_gbs, 1),
+        "pass_gemm_TFLOPs": round(2.0 * rows * shape.gemm_params / (ms_per_step * 1e-3) / 1e12, 1),
+        "attention_kv_stream_GBps": round((int(contexts.sum()) + rows) * shape.kv_bytes_per_token /
+                                          max(per_class.get("attention", 0.0), 1e-9) / 1e6, 1),
         "launch_mode": "hip graph replay" if graph is not None else "eager",
         "ms_per_step_eager": round(dt_eager * 1e3 / args.steps, 4),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_class.items()},
     }
     if not args.no_cpu_baseline:
         log("timing the CPU checker on the host cores ...")
-        result["cpu_baseline"] = cpu_baseline(shape, weights, window, prompt_len, seed)
+        result["cpu_baseline"] = cpu_baseline(shape, weights, window, int(min(contexts[0], 1024)), seed)
     sess.close()
     print(json.dumps(result), flush=True)
 

@@ -24,8 +24,8 @@
 // sequences: chunk partials are folded in registers, 8 times fewer partials go
 // through HBM) - for up to 8 blocks of 16 query rows of one (sequence, kv head);
 // query rows are ordered r = q_head_in_group * window + i.  K and V tiles are
-// fetched once per workgroup, 128 keys at a time, double buffered through LDS in
-// MFMA operand order (see the KV tile layouts in llm42.h), so no transpose is needed.
+// fetched once per workgroup, 128 keys at a time (the next stage's loads are issued
+// before the current stage is computed), double buffered through LDS in MFMA operand order (see the KV tile layouts in llm42.h), so no transpose is needed.
 #include "llm42_dev.h"
 
 namespace {
@@ -50,14 +50,17 @@ __device__ inline void fold(float& M, float& L, f32x4 (&A)[NV], float m2, float 
   M = mn;
 }
 
-typedef __attribute__((address_space(3))) void* lds_ptr;
-// Copy one KV tile (TL KiB) from global memory to LDS without passing through registers.
-// `src` already includes this lane's 16-byte offset; `dst` is the wave-uniform tile base.
+// A lane's share of one KV tile in flight between global memory and LDS: TL pieces of 16 bytes.
+// (Native vector type on purpose: register arrays of HIP_vector_type structs end up in scratch.)
 template <int TL>
-__device__ __forceinline__ void tile_to_lds(uint4* dst, const uint4* src) {
+__device__ __forceinline__ void tile_load(bf16x8 (&r)[TL], const uint4* src) {
 #pragma unroll
-  for (int i = 0; i < TL; ++i)
-    __builtin_amdgcn_global_load_lds((const void*)(src + i * 64), (lds_ptr)(dst + i * 64), 16, 0, 0);
+  for (int i = 0; i < TL; ++i) r[i] = ((const bf16x8*)src)[i * 64];
+}
+template <int TL>
+__device__ __forceinline__ void tile_store(uint4* dst, const bf16x8 (&r)[TL]) {
+#pragma unroll
+  for (int i = 0; i < TL; ++i) ((bf16x8*)dst)[i * 64] = r[i];
 }
 
 template <int HD, int CB, bool SUPER>
@@ -124,20 +127,26 @@ __global__ __launch_bounds__(256) void attention_kernel(
   const int ids0 = first_blk + lane <= last_blk ? raw0 : last_id;
   const int ids1 = first_blk + 64 + lane <= last_blk ? raw1 : last_id;
 
-  // each wave fetches two of the eight blocks of a stage, straight from global memory into LDS
-  // (no staging registers): one instruction moves 1 KiB, lane i's 16 bytes landing at base + 16 i
-#define ATT_FETCH(st_, buf_)                                                                   \
+  // each wave fetches two of the eight blocks of a stage into registers (issued before the current
+  // stage is computed) and parks them in the other LDS buffer afterwards
+  bf16x8 kreg0[TL], kreg1[TL], vreg0[TL], vreg1[TL];
+#define ATT_FETCH(st_)                                                                         \
   do {                                                                                         \
     const int bj_ = (st_) * 8 + wave * 2;               /* block index inside the unit */      \
     const int id0_ = __shfl(bj_ < 64 ? ids0 : ids1, bj_ & 63);                                 \
     const int id1_ = __shfl(bj_ + 1 < 64 ? ids0 : ids1, (bj_ + 1) & 63);                       \
-    tile_to_lds<TL>(&lds_k[buf_][(wave * 2) * TV4], k_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);     \
-    tile_to_lds<TL>(&lds_v[buf_][(wave * 2) * TV4], v_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);     \
-    tile_to_lds<TL>(&lds_k[buf_][(wave * 2 + 1) * TV4], k_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane); \
-    tile_to_lds<TL>(&lds_v[buf_][(wave * 2 + 1) * TV4], v_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane); \
+    tile_load<TL>(kreg0, k_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);            \
+    tile_load<TL>(vreg0, v_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);            \
+    tile_load<TL>(kreg1, k_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane);            \
+    tile_load<TL>(vreg1, v_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane);            \
   } while (0)
-  // all of this wave's outstanding fetches have landed in LDS
-#define ATT_LANDED() __builtin_amdgcn_s_waitcnt(0x0F70) /* vmcnt(0) */
+#define ATT_PARK(buf_)                                                                         \
+  do {                                                                                         \
+    tile_store<TL>(&lds_k[buf_][(wave * 2) * TV4 + lane], kreg0);                              \
+    tile_store<TL>(&lds_v[buf_][(wave * 2) * TV4 + lane], vreg0);                              \
+    tile_store<TL>(&lds_k[buf_][(wave * 2 + 1) * TV4 + lane], kreg1);                          \
+    tile_store<TL>(&lds_v[buf_][(wave * 2 + 1) * TV4 + lane], vreg1);                          \
+  } while (0)
 
   float m[CB], l[CB];
   f32x4 acc[CB][DB];
@@ -156,12 +165,12 @@ __global__ __launch_bounds__(256) void attention_kernel(
     }
   }
 
-  ATT_FETCH(0, 0);
-  ATT_LANDED();
+  ATT_FETCH(0);
+  ATT_PARK(0);
   __syncthreads();
   for (int st = 0; st < n_stages; ++st) {
     const int buf = st & 1;
-    if (st + 1 < n_stages) ATT_FETCH(st + 1, buf ^ 1);
+    if (st + 1 < n_stages) ATT_FETCH(st + 1);
     const uint16_t* vbase = (const uint16_t*)lds_v[buf];
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
@@ -274,7 +283,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
         for (int d = 0; d < DB; ++d) acc[cb][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
     }
-    ATT_LANDED();
+    if (st + 1 < n_stages) ATT_PARK(buf ^ 1);
     __syncthreads();
   }
 
@@ -291,7 +300,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
 }
 
 #undef ATT_FETCH
-#undef ATT_LANDED
+#undef ATT_PARK
 
 // Fold the partials of every query row (chunks inside a super left to right, then the supers
 // left to right) and write the normalised output, bf16, into the tile layout of the

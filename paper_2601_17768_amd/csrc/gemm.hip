@@ -13,10 +13,10 @@
 namespace {
 
 struct QkvEpi {
-  const float2* rope;        // [max_position][head_dim/2] (cos, sin)
-  const int32_t* row_pos;
-  const int32_t* row_seq;
-  const int32_t* block_table;
+  const float2* __restrict__ rope;        // [max_position][head_dim/2] (cos, sin)
+  const int32_t* __restrict__ row_pos;
+  const int32_t* __restrict__ row_seq;
+  const int32_t* __restrict__ block_table;
   uint16_t* q;               // [seq][kv head][r_pad][head_dim] tile layout, r = q-head-in-group * window + i
   uint16_t* k_plane;         // this layer's K tiles [block][kv head][16*head_dim]
   uint16_t* v_plane;
@@ -24,19 +24,29 @@ struct QkvEpi {
 
   // What the epilogue needs from memory besides the accumulators; requested when the kernel
   // starts so that its latency hides behind the weight stream.
-  struct Pre {
+  struct Row {   // per token row
+    int pos, s, blk;
+  };
+  struct Pre {   // per (token row, feature block)
     int pos, s, blk;
     float2 cs0, cs1;
   };
-  __device__ Pre pre(int nb, int lane, int row) const {
+  __device__ Row row_info(int row) const {
+    Row r;
+    r.pos = row_pos[row];
+    r.s = row_seq[row];
+    r.blk = block_table[(size_t)r.s * max_blocks_per_seq + (max(r.pos, 0) >> 4)];
+    return r;
+  }
+  __device__ Pre pre(int nb, int lane, int row, const Row& r) const {
     Pre p;
-    p.pos = row_pos[row];
-    p.s = row_seq[row];
-    const int safe = max(p.pos, 0);
+    p.pos = r.pos;
+    p.s = r.s;
+    p.blk = r.blk;
+    const int safe = max(r.pos, 0);
     const int j0 = (nb % (head_dim >> 4)) * 8 + (lane >> 4) * 2;
     p.cs0 = rope[(size_t)safe * (head_dim >> 1) + j0];
     p.cs1 = rope[(size_t)safe * (head_dim >> 1) + j0 + 1];
-    p.blk = block_table[(size_t)p.s * max_blocks_per_seq + (safe >> 4)];
     return p;
   }
   __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
@@ -81,10 +91,12 @@ struct QkvEpi {
 struct ResidualEpi {
   float* resid;   // fp32 residual stream [m_pad][n], updated in place (one lane owns each element)
   int n;
+  struct Row {};
   struct Pre {
     f32x4 old;
   };
-  __device__ Pre pre(int nb, int lane, int row) const {
+  __device__ Row row_info(int) const { return Row{}; }
+  __device__ Pre pre(int nb, int lane, int row, const Row&) const {
     return Pre{*(const f32x4*)(resid + resid_off(row, nb * 16 + (lane >> 4) * 4, n))};
   }
   __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
@@ -97,8 +109,10 @@ __device__ inline float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
 struct SwigluEpi {
   uint16_t* hidden;  // tile layout [m_pad][ffn_k]
   int ffn_k;
+  struct Row {};
   struct Pre {};
-  __device__ Pre pre(int, int, int) const { return Pre{}; }
+  __device__ Row row_info(int) const { return Row{}; }
+  __device__ Pre pre(int, int, int, const Row&) const { return Pre{}; }
   __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre&) const {
     // acc[0], acc[1]: gate of hidden features f, f+1;  acc[2], acc[3]: up of the same features
     const int f = nb * 8 + (lane >> 4) * 2;
@@ -114,16 +128,18 @@ struct LogitsEpi {
   float* out_logits;   // [n_dump][window][vocab] or null
   float2* amax;        // [m_pad][n_blocks]
   int window, vocab, n_blocks;
-  struct Pre {
+  struct Row {
     int pos, s, slot;
   };
-  __device__ Pre pre(int, int, int row) const {
-    Pre p;
+  typedef Row Pre;
+  __device__ Row row_info(int row) const {
+    Row p;
     p.pos = row_pos[row];
     p.s = row_seq[row];
     p.slot = out_logits ? dump_slot[p.s] : -1;
     return p;
   }
+  __device__ Pre pre(int, int, int, const Row& r) const { return r; }
   __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
     const int n0 = nb * 16 + (lane >> 4) * 4;
     if (out_logits && p.pos >= 0) {
@@ -192,15 +208,17 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const bf16x8* __restri
   for (int b = 0; b < MB; ++b) {
     const int row = (mb0 + b) * 16 + (lane & 15);
     if (ADD_PARTIAL) acc[b] = acc[b] + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
-    epi(nb, lane, row, acc[b], epi.pre(nb, lane, row));
+    epi(nb, lane, row, acc[b], epi.pre(nb, lane, row, epi.row_info(row)));
   }
 }
 
 struct StorePartialEpi {
   float* partial;   // [m_pad][n] in the residual-stream layout
   int n;
+  struct Row {};
   struct Pre {};
-  __device__ Pre pre(int, int, int) const { return Pre{}; }
+  __device__ Row row_info(int) const { return Row{}; }
+  __device__ Pre pre(int, int, int, const Row&) const { return Pre{}; }
   __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre&) const {
     *(f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n)) = acc;
   }
@@ -266,7 +284,7 @@ __global__ __launch_bounds__(256 * SPLIT) void gemm_coop_kernel(const bf16x8* __
   }
   if (my_rounds > 1) load_w(wb, 1);
   typename Epi::Pre pre{};
-  if (consumer && grp == 0) pre = epi.pre(nb, lane, gw * 16 + (lane & 15));
+  if (consumer && grp == 0) pre = epi.pre(nb, lane, gw * 16 + (lane & 15), epi.row_info(gw * 16 + (lane & 15)));
   for (int r = 0; r < rounds; r += 2) {
     round(wa, r);
     if (r + 1 < rounds) round(wb, r + 1);
@@ -336,7 +354,7 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   typename Epi::Pre pre[MB];
   if (owner) {
 #pragma unroll
-    for (int b = 0; b < MB; ++b) pre[b] = epi.pre(nb, lane, b * 16 + (lane & 15));
+    for (int b = 0; b < MB; ++b) pre[b] = epi.pre(nb, lane, b * 16 + (lane & 15), epi.row_info(b * 16 + (lane & 15)));
   }
   if (rounds > 0) store_x(0);
   __syncthreads();
@@ -391,13 +409,21 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   constexpr int ST = 2 * TB * KS;            // operand tiles per stage (weights then activations)
   constexpr int PW = ST / 4;                 // operand tiles each wave copies per stage
   __shared__ bf16x8 lds[2][ST * 64];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // wave index as a scalar, so that everything derived from it (operand addresses) stays in SGPRs
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wn = wave >> 1, wm = wave & 1;
-  // XCD-aware numbering: XCD (id % 8) gets a contiguous range of tiles, token tiles fastest
-  const int total = tiles_n * tiles_m, per_xcd = (total + 7) / 8;
-  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (t >= total || (blockIdx.x >> 3) >= per_xcd) return;
-  const int n0 = (t / tiles_m) * TB, m0 = (t % tiles_m) * TB;   // first feature / token block of the tile
+  // XCD-aware numbering.  Workgroup ids are dealt round-robin to the 8 XCDs; the 32 workgroups that
+  // run together on one XCD (consecutive ids of that XCD) form a super-tile of SN feature tiles x SM
+  // token tiles, so that per k-step the XCD's L2 fetches SN weight tiles + SM activation tiles for
+  // SN*SM workgroups.  Super-tiles are dealt to the XCDs round-robin.
+  constexpr int SN = 4, SM = 8;
+  const int sup_n = (tiles_n + SN - 1) / SN, sup_m = (tiles_m + SM - 1) / SM;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int sup = (local / (SN * SM)) * 8 + xcd, in_sup = local % (SN * SM);
+  if (sup >= sup_n * sup_m) return;
+  const int tn = (sup / sup_m) * SN + in_sup / SM, tm = (sup % sup_m) * SM + in_sup % SM;
+  if (tn >= tiles_n || tm >= tiles_m) return;
+  const int n0 = tn * TB, m0 = tm * TB;      // first feature / token block of the tile
 
   // source of the PW operand tiles this wave copies in every stage (k-tile added per stage)
   const bf16x8* src[PW];
@@ -418,7 +444,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
     for (int j = 0; j < WB; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const int stages = (k_count + KS - 1) / KS;
-  bf16x8 stg[PW];   // (a native vector type: arrays of HIP_vector_type structs end up in scratch)
+  // (Native vector types on purpose: register arrays of HIP_vector_type structs end up in scratch.)
+  // (Native vector types on purpose: register arrays of HIP_vector_type structs end up in scratch.
+  // A second staging set - two stages in flight - does not fit next to 256 accumulators: it spills.)
+  bf16x8 stg[PW];
   auto fetch = [&](int s) {      // k-tiles past the range re-read the last one (never used)
 #pragma unroll
     for (int i = 0; i < PW; ++i) stg[i] = src[i][(size_t)min(s * KS + kk_of[i], k_count - 1) * 64];
@@ -427,40 +456,65 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
 #pragma unroll
     for (int i = 0; i < PW; ++i) lds[buf][(wave * PW + i) * 64 + lane] = stg[i];
   };
+  // A full stage (KS k-tiles), software pipelined by hand: the activation operand needed three
+  // groups of WB MFMAs later and one weight operand of the next k-tile are requested from LDS BEFORE the
+  // current group is issued (the scheduling barriers keep the compiler from sinking the reads next to their
+  // uses, which would leave the MFMA pipe idle for an LDS latency after every group).
+  auto compute = [&](int s) {
+    const int buf = s & 1;
+    constexpr int PD = 3;                  // groups of WB MFMAs between an activation operand's request and its use
+    bf16x8 a[2][WB], bq[PD + 1];
+#pragma unroll
+    for (int i = 0; i < WB; ++i) a[0][i] = lds[buf][((wn * WB + i) * KS) * 64 + lane];
+#pragma unroll
+    for (int t = 0; t < PD; ++t) bq[t] = lds[buf][((TB + wm * WB + t % WB) * KS + t / WB) * 64 + lane];
+#pragma unroll
+    for (int t = 0; t < KS * WB; ++t) {
+      const int kk = t / WB, j = t % WB;
+      if (t + PD < KS * WB) {
+        const int kn = (t + PD) / WB, jn = (t + PD) % WB;
+        bq[(t + PD) % (PD + 1)] = lds[buf][((TB + wm * WB + jn) * KS + kn) * 64 + lane];
+      }
+      if (kk + 1 < KS) a[(kk + 1) & 1][j] = lds[buf][((wn * WB + j) * KS + kk + 1) * 64 + lane];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < WB; ++i) acc[i][j] = mfma16(a[kk & 1][i], bq[t % (PD + 1)], acc[i][j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  const int full = k_count / KS;           // full stages; an odd k_count leaves one k-tile for the tail
   fetch(0);
   park(0);
   __syncthreads();
-  for (int s = 0; s < stages; ++s) {
-    const int buf = s & 1;
+  for (int s = 0; s < full; ++s) {
     if (s + 1 < stages) fetch(s + 1);
-    const int kmax = min(KS, k_count - s * KS);
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      if (kk < kmax) {
-        bf16x8 a[WB];
-#pragma unroll
-        for (int i = 0; i < WB; ++i) a[i] = lds[buf][((wn * WB + i) * KS + kk) * 64 + lane];
-#pragma unroll
-        for (int j = 0; j < WB; ++j) {
-          const bf16x8 b = lds[buf][((TB + wm * WB + j) * KS + kk) * 64 + lane];
-#pragma unroll
-          for (int i = 0; i < WB; ++i) acc[i][j] = mfma16(a[i], b, acc[i][j]);
-        }
-      }
-    }
-    if (s + 1 < stages) park(buf ^ 1);
+    compute(s);
+    if (s + 1 < stages) park((s + 1) & 1);
     __syncthreads();
   }
-#pragma unroll
-  for (int i = 0; i < WB; ++i) {
-    const int nb = n0 + wn * WB + i;
-    if (nb >= n_blocks) continue;
+  if (full < stages) {                     // tail stage holding a single k-tile (kk = 0)
+    const int buf = full & 1;
 #pragma unroll
     for (int j = 0; j < WB; ++j) {
-      const int row = (m0 + wm * WB + j) * 16 + (lane & 15);
-      f32x4 v = acc[i][j];
-      if (ADD_PARTIAL) v = v + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
-      epi(nb, lane, row, v, epi.pre(nb, lane, row));
+      const bf16x8 b = lds[buf][((TB + wm * WB + j) * KS) * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < WB; ++i)
+        acc[i][j] = mfma16(lds[buf][((wn * WB + i) * KS) * 64 + lane], b, acc[i][j]);
+    }
+  }
+  // epilogue, token block by token block: what depends on the token row only is fetched once per row
+#pragma unroll
+  for (int j = 0; j < WB; ++j) {
+    const int row = (m0 + wm * WB + j) * 16 + (lane & 15);
+    const typename Epi::Row ri = epi.row_info(row);
+#pragma unroll
+    for (int i = 0; i < WB; ++i) {
+      const int nb = n0 + wn * WB + i;
+      if (nb < n_blocks) {
+        f32x4 v = acc[i][j];
+        if (ADD_PARTIAL) v = v + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
+        epi(nb, lane, row, v, epi.pre(nb, lane, row, ri));
+      }
     }
   }
 }
@@ -469,7 +523,8 @@ template <int WB, int SPLIT, class Epi>
 void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles, int n, const Workspace& ws,
                   const Epi& epi, hipStream_t st) {
   const int tb = 2 * WB, tiles_n = (n_blocks + tb - 1) / tb, tiles_m = ws.m_pad / (16 * tb);
-  const unsigned grid = 8u * (unsigned)((tiles_n * tiles_m + 7) / 8);
+  const int supers = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);      // super-tiles of 4 x 8 tiles, 8 XCDs
+  const unsigned grid = 8u * 32u * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
     gemm_tiled_kernel<WB, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr, n, tiles_n,
                                                             tiles_m, epi);
