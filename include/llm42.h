@@ -98,7 +98,8 @@ typedef struct {
  * 16 * head_dim bf16 values, indexed [layer][0 = K, 1 = V][block][kv_head].
  * Inside a tile (token t = position % 16, feature f):
  *   K tile: element index ((f / 8) * 16 + t) * 8 + f % 8     (8-feature groups, token-minor)
- *   V tile: element index  f * 16 + t                        (feature-major)
+ *   V tile: element index (((f / 16) * 4 + t / 4) * 16 + f % 16) * 4 + t % 4
+ *                                         (16-feature blocks, 4-token groups, feature, token-minor)
  * Position p of sequence s lives in block block_table[s][p / 16].
  * llm42_kv_bytes() gives the size of the whole cache. */
 typedef struct {

@@ -23,6 +23,12 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",
 ]
+# Per-file additions.  The attention kernels keep their MFMA accumulators in ordinary vector
+# registers: the softmax rescales them with vector arithmetic at every step, and accumulators
+# placed in the accumulation registers would be copied out and back each time.
+FILE_FLAGS = {
+    "attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
 
 
 def sources():
@@ -36,7 +42,7 @@ def build(verbose: bool = True) -> str:
 
     def compile_one(pair):
         src, obj = pair
-        cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+        cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), "-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         return src, r
 

@@ -26,17 +26,17 @@
 // query rows are ordered r = q_head_in_group * window + i.  K and V tiles are
 // fetched once per workgroup, 128 keys at a time (the next stage's loads are issued
 // before the current stage is computed), double buffered through LDS in MFMA operand order (see the KV tile layouts in llm42.h), so no transpose is needed.
+#include <type_traits>
+
 #include "llm42_dev.h"
 
 namespace {
 
 constexpr int STEP = 64, CHUNK = 256, SUPER_KEYS = 2048, STAGE = 128;
 
-union Frag {
-  bf16x8 v;
-  uint4 u;
-  uint2 h[2];
-};
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
 // state <- state (+) part, the only way two partials are ever combined.
 template <int NV>
@@ -50,17 +50,43 @@ __device__ inline void fold(float& M, float& L, f32x4 (&A)[NV], float m2, float 
   M = mn;
 }
 
-// A lane's share of one KV tile in flight between global memory and LDS: TL pieces of 16 bytes.
-// (Native vector type on purpose: register arrays of HIP_vector_type structs end up in scratch.)
+// Copy one KV tile (TL KiB) from global memory to LDS without passing through registers: one
+// instruction moves 1 KiB, lane i's 16 bytes landing at LDS byte address `dst` + 16 i (M0 holds the
+// wave-uniform destination).  `src` already includes this lane's 16-byte offset.  Written as
+// assembly on purpose: with the compiler's own form of this load every later LDS read waits for
+// all earlier ones, which un-pipelines the operand reads of the steps.  The compiler therefore
+// does not count these loads; fetch_landed() is the only wait that covers them.  Nothing else in
+// this kernel uses M0.
 template <int TL>
-__device__ __forceinline__ void tile_load(bf16x8 (&r)[TL], const uint4* src) {
+__device__ __forceinline__ void tile_to_lds(uint32_t dst, const uint4* src) {
 #pragma unroll
-  for (int i = 0; i < TL; ++i) r[i] = ((const bf16x8*)src)[i * 64];
+  for (int i = 0; i < TL; ++i)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src + i * 64), "s"(dst + i * 1024)
+                 : "memory");
 }
-template <int TL>
-__device__ __forceinline__ void tile_store(uint4* dst, const bf16x8 (&r)[TL]) {
-#pragma unroll
-  for (int i = 0; i < TL; ++i) ((bf16x8*)dst)[i * 64] = r[i];
+// Every fetch this wave has issued is in LDS (the barrier that follows covers the other waves').
+// (Both forms of the wait: the first tells the compiler that its own loads are complete as well.)
+__device__ __forceinline__ void fetch_landed() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// Butterflies over the four 16-lane rows of a wave (lane ^ 16, then lane ^ 32) without a trip
+// through LDS: a swap leaves the two partners of every lane in the two results, and max / + are
+// commutative, so each lane gets the same bits as from the shuffle form of the butterfly.
+__device__ __forceinline__ float rows_max(float x) {
+  u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r.x) + __uint_as_float(r.y);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r.x) + __uint_as_float(r.y);
 }
 
 template <int HD, int CB, bool SUPER>
@@ -74,11 +100,11 @@ __global__ __launch_bounds__(256) void attention_kernel(
   constexpr int TV4 = HD * 2;        // uint4 per KV tile (16 tokens x HD bf16)
   constexpr int TL = TV4 / 64;       // uint4 per lane per tile
   constexpr int UNIT = SUPER ? SUPER_KEYS : CHUNK;
-  __shared__ uint4 lds_k[2][8 * TV4];
-  __shared__ uint4 lds_v[2][8 * TV4];
+  __shared__ uint4 lds_k[2][8 * TV4];   // two stage buffers of 8 K tiles
+  __shared__ uint4 lds_v[2][8 * TV4];   // and of 8 V tiles
   __shared__ int wg_max[4];
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 15, g = lane >> 4;
   const int unit = blockIdx.x;
   const int s = blockIdx.z / n_kv_heads, kvh = blockIdx.z % n_kv_heads;
@@ -90,7 +116,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
   const int first_blk = k_lo >> 4;
   const int raw0 = bt[min(first_blk + lane, max_blocks_per_seq - 1)];
   const int raw1 = SUPER ? bt[min(first_blk + 64 + lane, max_blocks_per_seq - 1)] : 0;
-  Frag qf[CB][DK];
+  bf16x8 qf[CB][DK];
   int row[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
@@ -99,21 +125,26 @@ __global__ __launch_bounds__(256) void attention_kernel(
     const int rb = min(row[cb] >> 4, r_pad / 16 - 1);
     const uint16_t* qb = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)rb * DK * 512;
 #pragma unroll
-    for (int d = 0; d < DK; ++d) qf[cb][d].u = *(const uint4*)(qb + d * 512 + lane * 8);
+    for (int d = 0; d < DK; ++d) qf[cb][d] = *(const bf16x8*)(qb + d * 512 + lane * 8);
   }
   const int L = seq_len[s], n = seq_n[s];
   if (L < 0) return;                                         // whole workgroup
 
   int qpos[CB];
-  int wmax = -1;
+  int wmax = -1, wmin = 0x7FFFFFFF;   // highest and lowest position among this wave's rows (dead rows: -1)
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     const int i = row[cb] % window;
     qpos[cb] = (row[cb] < group * window && i < n) ? L + i : -1;
     wmax = max(wmax, qpos[cb]);
+    wmin = min(wmin, qpos[cb]);
   }
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off));
+  for (int off = 1; off < 64; off <<= 1) {
+    wmax = max(wmax, __shfl_xor(wmax, off));
+    wmin = min(wmin, __shfl_xor(wmin, off));
+  }
+  wmin = __builtin_amdgcn_readfirstlane(wmin);
   if (lane == 0) wg_max[wave] = wmax;
   __syncthreads();
   const int gmax = max(max(wg_max[0], wg_max[1]), max(wg_max[2], wg_max[3]));
@@ -127,26 +158,19 @@ __global__ __launch_bounds__(256) void attention_kernel(
   const int ids0 = first_blk + lane <= last_blk ? raw0 : last_id;
   const int ids1 = first_blk + 64 + lane <= last_blk ? raw1 : last_id;
 
-  // each wave fetches two of the eight blocks of a stage into registers (issued before the current
-  // stage is computed) and parks them in the other LDS buffer afterwards
-  bf16x8 kreg0[TL], kreg1[TL], vreg0[TL], vreg1[TL];
-#define ATT_FETCH(st_)                                                                         \
-  do {                                                                                         \
-    const int bj_ = (st_) * 8 + wave * 2;               /* block index inside the unit */      \
-    const int id0_ = __shfl(bj_ < 64 ? ids0 : ids1, bj_ & 63);                                 \
-    const int id1_ = __shfl(bj_ + 1 < 64 ? ids0 : ids1, (bj_ + 1) & 63);                       \
-    tile_load<TL>(kreg0, k_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);            \
-    tile_load<TL>(vreg0, v_plane + ((size_t)id0_ * n_kv_heads + kvh) * TV4 + lane);            \
-    tile_load<TL>(kreg1, k_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane);            \
-    tile_load<TL>(vreg1, v_plane + ((size_t)id1_ * n_kv_heads + kvh) * TV4 + lane);            \
-  } while (0)
-#define ATT_PARK(buf_)                                                                         \
-  do {                                                                                         \
-    tile_store<TL>(&lds_k[buf_][(wave * 2) * TV4 + lane], kreg0);                              \
-    tile_store<TL>(&lds_v[buf_][(wave * 2) * TV4 + lane], vreg0);                              \
-    tile_store<TL>(&lds_k[buf_][(wave * 2 + 1) * TV4 + lane], kreg1);                          \
-    tile_store<TL>(&lds_v[buf_][(wave * 2 + 1) * TV4 + lane], vreg1);                          \
-  } while (0)
+  // each wave fetches two of the eight blocks of a stage, straight from global memory into LDS
+  const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_k[0][0];
+  const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_v[0][0];
+  auto fetch = [&](int st, int buf) {
+    const int bj = st * 8 + wave * 2;                        // block index inside the unit
+    const int id0 = __shfl(bj < 64 ? ids0 : ids1, bj & 63);
+    const int id1 = __shfl(bj + 1 < 64 ? ids0 : ids1, (bj + 1) & 63);
+    const uint32_t off = (uint32_t)((buf * 8 + wave * 2) * TV4) * 16;
+    tile_to_lds<TL>(lds_k_addr + off, k_plane + ((size_t)id0 * n_kv_heads + kvh) * TV4 + lane);
+    tile_to_lds<TL>(lds_v_addr + off, v_plane + ((size_t)id0 * n_kv_heads + kvh) * TV4 + lane);
+    tile_to_lds<TL>(lds_k_addr + off + TV4 * 16, k_plane + ((size_t)id1 * n_kv_heads + kvh) * TV4 + lane);
+    tile_to_lds<TL>(lds_v_addr + off + TV4 * 16, v_plane + ((size_t)id1 * n_kv_heads + kvh) * TV4 + lane);
+  };
 
   float m[CB], l[CB];
   f32x4 acc[CB][DB];
@@ -165,105 +189,134 @@ __global__ __launch_bounds__(256) void attention_kernel(
     }
   }
 
-  ATT_FETCH(0);
-  ATT_PARK(0);
-  __syncthreads();
-  for (int st = 0; st < n_stages; ++st) {
-    const int buf = st & 1;
-    if (st + 1 < n_stages) ATT_FETCH(st + 1);
-    const uint16_t* vbase = (const uint16_t*)lds_v[buf];
+  // One online-softmax step over the 64 keys [k0, k0 + 64): `lk` / `lv` are the step's four K and
+  // four V tiles in LDS.  MASKED = false is the same arithmetic with the comparisons that cannot
+  // fail left out: every key of the step is at or below every position of this wave's rows (and
+  // hence below k_hi).  With one wave per SIMD nothing hides an LDS round trip, so the operand
+  // reads are issued one group ahead of the MFMAs that consume them and the order is pinned.
+  auto step = [&](auto masked_c, const uint4* lk, const uint16_t* lv, int k0) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    constexpr int RV = 4;                                     // V operands in flight
+    bf16x8 kb[DK];                                            // K operands in flight, one per head-dim k-step
+    u32x4 vb[RV];
+    auto load_k = [&](int b, int d) { kb[d] = ((const bf16x8*)lk)[b * TV4 + d * 64 + lane]; };
+    auto load_v = [&](int idx) {                              // idx = key pair kk * DB + feature block d
+      const uint16_t* vt0 = lv + (size_t)(2 * (idx / DB)) * TV4 * 8 + (((idx % DB) * 4 + g) * 16 + col) * 4;
+      const u32x2 lo = *(const u32x2*)vt0, hi = *(const u32x2*)(vt0 + TV4 * 8);
+      vb[idx % RV] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+    };
+    // ---- raw scores of 4 blocks of 16 keys: S^T[key][query] ---------------------------------
+    f32x4 sc[CB][4];
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      const int k0 = k_lo + st * STAGE + s2 * STEP;
-      if (k0 >= k_hi) break;                                  // workgroup-uniform
-      // ---- scores of 4 blocks of 16 keys: S^T[key][query] ---------------------------------
-      f32x4 sc[CB][4];
+    for (int d = 0; d < DK; ++d) load_k(0, d);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < 4; ++b) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) sc[cb][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (k0 + b * 16 < k_hi) {                            // workgroup-uniform
+      for (int d = 0; d < DK; ++d) {
 #pragma unroll
-          for (int d = 0; d < DK; ++d) {
-            Frag kf;
-            kf.u = lds_k[buf][(s2 * 4 + b) * TV4 + d * 64 + lane];
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) sc[cb][b] = mfma16(kf.v, qf[cb][d].v, sc[cb][b]);
-          }
-        }
+        for (int cb = 0; cb < CB; ++cb)
+          sc[cb][b] = mfma16(kb[d], qf[cb][d], d == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : sc[cb][b]);
+        if (b + 1 < 4) load_k(b + 1, d);
+        else if (d < RV) load_v(d);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // ---- mask, online softmax state, P in bf16 ------------------------------------------
-      Frag pf[CB][2];
+    }
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) {
-        float mx = -INFINITY;
+    for (int i = DK; i < RV; ++i) load_v(i);
+    // ---- mask, online softmax state (m in units of scaled scores), P in bf16 -----------------
+    u32x4 pf[CB][2];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      if (MASKED) {
+        // a select, not arithmetic: scores of keys past k_hi come from stale tiles and may be anything
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int kpos = k0 + b * 16 + g * 4 + e;
-            const float v = kpos <= qpos[cb] ? sc[cb][b][e] * scale_log2 : -INFINITY;
-            sc[cb][b][e] = v;
-            mx = fmaxf(mx, v);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m[cb], mx);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m[cb] - m_use);
-        float rs = 0.f;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) sc[cb][b][e] = __builtin_amdgcn_exp2f(sc[cb][b][e] - m_use);
-          rs += ((sc[cb][b][0] + sc[cb][b][1]) + sc[cb][b][2]) + sc[cb][b][3];
-        }
-        rs += __shfl_xor(rs, 16);
-        rs += __shfl_xor(rs, 32);
-        l[cb] = l[cb] * alpha + rs;
-        m[cb] = m_new;
-#pragma unroll
-        for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
-        // k-slot e of lane group g is key g*4+e of the first block of a pair (e < 4) or of the
-        // second (e >= 4); V below uses the same assignment
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          pf[cb][kk].h[0].x = pack2_bf16(sc[cb][2 * kk][0], sc[cb][2 * kk][1]);
-          pf[cb][kk].h[0].y = pack2_bf16(sc[cb][2 * kk][2], sc[cb][2 * kk][3]);
-          pf[cb][kk].h[1].x = pack2_bf16(sc[cb][2 * kk + 1][0], sc[cb][2 * kk + 1][1]);
-          pf[cb][kk].h[1].y = pack2_bf16(sc[cb][2 * kk + 1][2], sc[cb][2 * kk + 1][3]);
-        }
+          for (int e = 0; e < 4; ++e)
+            if (k0 + b * 16 + g * 4 + e > qpos[cb]) sc[cb][b][e] = -INFINITY;
       }
-      // ---- acc^T[feature][query] += V^T P^T, 32 keys per MFMA ------------------------------
+      float mx = fmaxf(fmaxf(sc[cb][0][0], sc[cb][0][1]), sc[cb][0][2]);
+      mx = fmaxf(fmaxf(mx, sc[cb][0][3]), sc[cb][1][0]);
+      mx = fmaxf(fmaxf(mx, sc[cb][1][1]), sc[cb][1][2]);
+      mx = fmaxf(fmaxf(mx, sc[cb][1][3]), sc[cb][2][0]);
+      mx = fmaxf(fmaxf(mx, sc[cb][2][1]), sc[cb][2][2]);
+      mx = fmaxf(fmaxf(mx, sc[cb][2][3]), sc[cb][3][0]);
+      mx = fmaxf(fmaxf(mx, sc[cb][3][1]), sc[cb][3][2]);
+      mx = rows_max(fmaxf(mx, sc[cb][3][3]));
+      // scaling by a positive constant is monotonic: max(scaled) == scaled(max), bit for bit
+      const float m_new = fmaxf(m[cb], mx * scale_log2);
+      const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m[cb] - m_use);
+      float rs = 0.f;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          sc[cb][b][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cb][b][e], scale_log2, -m_use));
+        rs += ((sc[cb][b][0] + sc[cb][b][1]) + sc[cb][b][2]) + sc[cb][b][3];
+      }
+      rs = rows_sum(rs);
+      l[cb] = l[cb] * alpha + rs;
+      m[cb] = m_new;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
+      // k-slot e of lane group g is key g*4+e of the first block of a pair (e < 4) or of the
+      // second (e >= 4); V uses the same assignment
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
+        pf[cb][kk][0] = pack2_bf16(sc[cb][2 * kk][0], sc[cb][2 * kk][1]);
+        pf[cb][kk][1] = pack2_bf16(sc[cb][2 * kk][2], sc[cb][2 * kk][3]);
+        pf[cb][kk][2] = pack2_bf16(sc[cb][2 * kk + 1][0], sc[cb][2 * kk + 1][1]);
+        pf[cb][kk][3] = pack2_bf16(sc[cb][2 * kk + 1][2], sc[cb][2 * kk + 1][3]);
+      }
+    }
+    // ---- acc^T[feature][query] += V^T P^T, 32 keys per MFMA ------------------------------
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int idx = 0; idx < 2 * DB; ++idx) {
+      const int kk = idx / DB, d = idx % DB;
+      if (MASKED) {
+        // slots at or beyond k_hi hold stale, never-written or foreign data: force them to zero
+        // so that 0 * garbage cannot produce a NaN
         const int kp0 = k0 + kk * 32 + g * 4, kp1 = kp0 + 16;
-        if (k0 + kk * 32 >= k_hi) break;                      // workgroup-uniform
-        const uint16_t* vt0 = vbase + (size_t)(s2 * 4 + 2 * kk) * TV4 * 8;
-        const uint16_t* vt1 = vt0 + TV4 * 8;
-#pragma unroll
-        for (int d = 0; d < DB; ++d) {
-          Frag vf;
-          vf.h[0] = *(const uint2*)(vt0 + (d * 16 + col) * 16 + g * 4);
-          vf.h[1] = *(const uint2*)(vt1 + (d * 16 + col) * 16 + g * 4);
-          // slots at or beyond k_hi hold stale, never-written or foreign data: force them to zero
-          // so that 0 * garbage cannot produce a NaN
-          if (kp0 + 3 >= k_hi) {
-            if (kp0 + 0 >= k_hi) vf.h[0].x &= 0xFFFF0000u;
-            if (kp0 + 1 >= k_hi) vf.h[0].x &= 0x0000FFFFu;
-            if (kp0 + 2 >= k_hi) vf.h[0].y &= 0xFFFF0000u;
-            if (kp0 + 3 >= k_hi) vf.h[0].y &= 0x0000FFFFu;
-          }
-          if (kp1 + 3 >= k_hi) {
-            if (kp1 + 0 >= k_hi) vf.h[1].x &= 0xFFFF0000u;
-            if (kp1 + 1 >= k_hi) vf.h[1].x &= 0x0000FFFFu;
-            if (kp1 + 2 >= k_hi) vf.h[1].y &= 0xFFFF0000u;
-            if (kp1 + 3 >= k_hi) vf.h[1].y &= 0x0000FFFFu;
-          }
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) acc[cb][d] = mfma16(vf.v, pf[cb][kk].v, acc[cb][d]);
+        if (kp1 + 3 >= k_hi) {
+          u32x4& v = vb[idx % RV];
+          if (kp0 + 0 >= k_hi) v[0] &= 0xFFFF0000u;
+          if (kp0 + 1 >= k_hi) v[0] &= 0x0000FFFFu;
+          if (kp0 + 2 >= k_hi) v[1] &= 0xFFFF0000u;
+          if (kp0 + 3 >= k_hi) v[1] &= 0x0000FFFFu;
+          if (kp1 + 0 >= k_hi) v[2] &= 0xFFFF0000u;
+          if (kp1 + 1 >= k_hi) v[2] &= 0x0000FFFFu;
+          if (kp1 + 2 >= k_hi) v[3] &= 0xFFFF0000u;
+          if (kp1 + 3 >= k_hi) v[3] &= 0x0000FFFFu;
         }
       }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+        acc[cb][d] = mfma16(__builtin_bit_cast(bf16x8, vb[idx % RV]), __builtin_bit_cast(bf16x8, pf[cb][kk]),
+                            acc[cb][d]);
+      if (idx + RV < 2 * DB) load_v(idx + RV);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  fetch(0, 0);
+  fetch_landed();
+  __syncthreads();
+  for (int st = 0; st < n_stages; ++st) {
+    // start the fetch of the next stage into the other buffer, run this stage's (up to) two steps,
+    // close a chunk if one ends here, and meet the other waves once the fetch has landed
+    const int buf = st & 1;
+    if (st + 1 < n_stages) fetch(st + 1, buf ^ 1);
+#pragma nounroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int k0 = k_lo + st * STAGE + s2 * STEP;
+      if (k0 >= k_hi) break;                                  // workgroup-uniform
+      const uint4* sk = &lds_k[buf][s2 * 4 * TV4];
+      const uint16_t* sv = (const uint16_t*)&lds_v[buf][s2 * 4 * TV4];
+      if (k0 + STEP - 1 <= wmin) step(std::false_type{}, sk, sv, k0);    // wave-uniform
+      else step(std::true_type{}, sk, sv, k0);
     }
     if (SUPER && ((st & 1) || st + 1 == n_stages)) {
       // a chunk is complete: fold it into the running super partial and start the next one afresh
@@ -283,7 +336,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
         for (int d = 0; d < DB; ++d) acc[cb][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
     }
-    if (st + 1 < n_stages) ATT_PARK(buf ^ 1);
+    fetch_landed();
     __syncthreads();
   }
 
@@ -298,9 +351,6 @@ __global__ __launch_bounds__(256) void attention_kernel(
     if (g == 0) *(float2*)(part_ml + prow * 2) = SUPER ? make_float2(sm[cb], sl[cb]) : make_float2(m[cb], l[cb]);
   }
 }
-
-#undef ATT_FETCH
-#undef ATT_PARK
 
 // Fold the partials of every query row (chunks inside a super left to right, then the supers
 // left to right) and write the normalised output, bf16, into the tile layout of the

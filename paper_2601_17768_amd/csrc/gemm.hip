@@ -80,10 +80,10 @@ struct QkvEpi {
       *(uint32_t*)(tile + (((j0 + half) >> 3) * 16 + tok) * 8 + (j0 & 7)) = hi;
     } else {
       uint16_t* tile = v_plane + ((size_t)blk * n_kv_heads + (head - n_q_heads - n_kv_heads)) * 16 * head_dim;
-      tile[j0 * 16 + tok] = (uint16_t)lo;
-      tile[(j0 + 1) * 16 + tok] = (uint16_t)(lo >> 16);
-      tile[(j0 + half) * 16 + tok] = (uint16_t)hi;
-      tile[(j0 + half + 1) * 16 + tok] = (uint16_t)(hi >> 16);
+      tile[v_tile_off(j0, tok)] = (uint16_t)lo;
+      tile[v_tile_off(j0 + 1, tok)] = (uint16_t)(lo >> 16);
+      tile[v_tile_off(j0 + half, tok)] = (uint16_t)hi;
+      tile[v_tile_off(j0 + half + 1, tok)] = (uint16_t)(hi >> 16);
     }
   }
 };

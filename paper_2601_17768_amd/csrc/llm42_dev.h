@@ -45,8 +45,18 @@ __device__ inline uint32_t f32_to_bf16_bits(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// the same rounding for two values at once, by the hardware conversion (one instruction on gfx950)
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ inline uint32_t pack2_bf16(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// V tile of the KV cache: [feature block of 16][token group of 4][feature][4 tokens], the order in
+// which the lanes of a P V operand read it (8 contiguous bytes per lane, 512 per wave).
+__host__ __device__ inline int v_tile_off(int f, int t) {
+  return (((f >> 4) * 4 + (t >> 2)) * 16 + (f & 15)) * 4 + (t & 3);
 }
 
 __device__ inline f32x4 mfma16(const bf16x8 a, const bf16x8 b, const f32x4 c) {

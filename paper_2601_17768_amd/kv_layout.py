@@ -21,9 +21,9 @@ def _tiles_to_tokens_k(t: torch.Tensor, hd: int) -> torch.Tensor:
 
 
 def _tiles_to_tokens_v(t: torch.Tensor, hd: int) -> torch.Tensor:
-    # V tile order (feature, token) -> [L, nb*16, H, hd]
+    # V tile order (feature block of 16, token group of 4, feature, token) -> [L, nb*16, H, hd]
     L, nb, H, _ = t.shape
-    return t.view(L, nb, H, hd, 16).permute(0, 1, 4, 2, 3).reshape(L, nb * 16, H, hd)
+    return t.view(L, nb, H, hd // 16, 4, 16, 4).permute(0, 1, 4, 6, 2, 3, 5).reshape(L, nb * 16, H, hd)
 
 
 def _tokens_to_tiles_k(x: torch.Tensor, hd: int) -> torch.Tensor:
@@ -33,7 +33,7 @@ def _tokens_to_tiles_k(x: torch.Tensor, hd: int) -> torch.Tensor:
 
 def _tokens_to_tiles_v(x: torch.Tensor, hd: int) -> torch.Tensor:
     L, T, H, _ = x.shape
-    return x.view(L, T // 16, 16, H, hd).permute(0, 1, 3, 4, 2).reshape(L, T // 16, H, 16 * hd)
+    return x.view(L, T // 16, 4, 4, H, hd // 16, 16).permute(0, 1, 4, 5, 2, 6, 3).reshape(L, T // 16, H, 16 * hd)
 
 
 def read_tokens(kv: torch.Tensor, block_ids: torch.Tensor, length: int, head_dim: int):
