@@ -32,7 +32,7 @@
 
 namespace {
 
-constexpr int STEP = 64, CHUNK = 256, SUPER_KEYS = 2048, STAGE = 128;
+constexpr int STEP = 64, CHUNK = 256, SUPER_KEYS = 2048;
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -66,7 +66,13 @@ __device__ __forceinline__ void tile_to_lds(uint32_t dst, const uint4* src) {
                  : "v"(src + i * 64), "s"(dst + i * 1024)
                  : "memory");
 }
-// Every fetch this wave has issued is in LDS (the barrier that follows covers the other waves').
+// At most N of the fetches this wave has issued are still on their way (they complete in order;
+// the barrier that follows covers the other waves').
+template <int N>
+__device__ __forceinline__ void fetch_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+// Every fetch this wave has issued is in LDS.
 // (Both forms of the wait: the first tells the compiler that its own loads are complete as well.)
 __device__ __forceinline__ void fetch_landed() {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -89,8 +95,8 @@ __device__ __forceinline__ float rows_sum(float x) {
   return __uint_as_float(r.x) + __uint_as_float(r.y);
 }
 
-template <int HD, int CB, bool SUPER>
-__global__ __launch_bounds__(256) void attention_kernel(
+template <int HD, int CB, int NW, bool SUPER>
+__global__ __launch_bounds__(NW * 64) void attention_kernel(
     const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
     int n_kv_heads, int group, int window, int r_pad, int max_blocks_per_seq, int n_units, float scale_log2,
@@ -100,9 +106,13 @@ __global__ __launch_bounds__(256) void attention_kernel(
   constexpr int TV4 = HD * 2;        // uint4 per KV tile (16 tokens x HD bf16)
   constexpr int TL = TV4 / 64;       // uint4 per lane per tile
   constexpr int UNIT = SUPER ? SUPER_KEYS : CHUNK;
-  __shared__ uint4 lds_k[2][8 * TV4];   // two stage buffers of 8 K tiles
-  __shared__ uint4 lds_v[2][8 * TV4];   // and of 8 V tiles
-  __shared__ int wg_max[4];
+  constexpr int NBUF = 4, AHEAD = 3;    // ring of step buffers; steps in flight ahead of the one computed
+  constexpr int FI = 8 * TL / NW;       // fetch instructions per wave per step (4 K and 4 V tiles in all)
+  static_assert(NW == 4 || NW == 8, "a step's tiles are split over 4 or 8 waves");
+  static_assert(TL % (NW / 4) == 0, "half a tile per wave needs an even number of pieces");
+  __shared__ uint4 lds_k[NBUF][4 * TV4];   // per step: 4 K tiles
+  __shared__ uint4 lds_v[NBUF][4 * TV4];   // and 4 V tiles
+  __shared__ int wg_max[NW];
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 15, g = lane >> 4;
@@ -120,7 +130,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
   int row[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
-    row[cb] = ((blockIdx.y * 4 + wave) * CB + cb) * 16 + col;
+    row[cb] = ((blockIdx.y * NW + wave) * CB + cb) * 16 + col;
     // row blocks past r_pad (grid padding) read the last real block instead; their rows are dead anyway
     const int rb = min(row[cb] >> 4, r_pad / 16 - 1);
     const uint16_t* qb = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)rb * DK * 512;
@@ -147,10 +157,12 @@ __global__ __launch_bounds__(256) void attention_kernel(
   wmin = __builtin_amdgcn_readfirstlane(wmin);
   if (lane == 0) wg_max[wave] = wmax;
   __syncthreads();
-  const int gmax = max(max(wg_max[0], wg_max[1]), max(wg_max[2], wg_max[3]));
+  int gmax = wg_max[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) gmax = max(gmax, wg_max[w]);
   if (gmax < k_lo) return;                                   // whole workgroup: nobody looks into this unit
   const int k_hi = min(gmax + 1, k_lo + UNIT);               // exclusive; <= L + n
-  const int n_stages = (k_hi - k_lo + STAGE - 1) / STAGE;
+  const int n_steps = (k_hi - k_lo + STEP - 1) / STEP;
   const int last_blk = (k_hi - 1) >> 4;
   // table entries past the last needed block may hold anything: replace them by the last needed
   // block's id (its data is fetched in their place, and every key in those positions is masked)
@@ -158,18 +170,19 @@ __global__ __launch_bounds__(256) void attention_kernel(
   const int ids0 = first_blk + lane <= last_blk ? raw0 : last_id;
   const int ids1 = first_blk + 64 + lane <= last_blk ? raw1 : last_id;
 
-  // each wave fetches two of the eight blocks of a stage, straight from global memory into LDS
+  // each wave fetches one (4 waves) or half (8 waves) of the four blocks of a step, its K and its V
+  // tile, straight from global memory into LDS
   const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_k[0][0];
   const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_v[0][0];
-  auto fetch = [&](int st, int buf) {
-    const int bj = st * 8 + wave * 2;                        // block index inside the unit
-    const int id0 = __shfl(bj < 64 ? ids0 : ids1, bj & 63);
-    const int id1 = __shfl(bj + 1 < 64 ? ids0 : ids1, (bj + 1) & 63);
-    const uint32_t off = (uint32_t)((buf * 8 + wave * 2) * TV4) * 16;
-    tile_to_lds<TL>(lds_k_addr + off, k_plane + ((size_t)id0 * n_kv_heads + kvh) * TV4 + lane);
-    tile_to_lds<TL>(lds_v_addr + off, v_plane + ((size_t)id0 * n_kv_heads + kvh) * TV4 + lane);
-    tile_to_lds<TL>(lds_k_addr + off + TV4 * 16, k_plane + ((size_t)id1 * n_kv_heads + kvh) * TV4 + lane);
-    tile_to_lds<TL>(lds_v_addr + off + TV4 * 16, v_plane + ((size_t)id1 * n_kv_heads + kvh) * TV4 + lane);
+  auto fetch = [&](int j) {
+    constexpr int SPLIT = NW / 4, PIECES = TL / SPLIT;       // waves per block; 1 KiB pieces per wave and tile
+    const int blk = wave / SPLIT, part = wave % SPLIT;
+    const int bj = j * 4 + blk;                              // block index inside the unit (wave-uniform)
+    const int id = bj < 64 ? __builtin_amdgcn_readlane(ids0, bj & 63) : __builtin_amdgcn_readlane(ids1, bj & 63);
+    const uint32_t off = (uint32_t)(((j & (NBUF - 1)) * 4 + blk) * TV4 + part * PIECES * 64) * 16;
+    const size_t src = ((size_t)id * n_kv_heads + kvh) * TV4 + part * PIECES * 64 + lane;
+    tile_to_lds<PIECES>(lds_k_addr + off, k_plane + src);
+    tile_to_lds<PIECES>(lds_v_addr + off, v_plane + src);
   };
 
   float m[CB], l[CB];
@@ -301,28 +314,28 @@ __global__ __launch_bounds__(256) void attention_kernel(
     }
   };
 
-  fetch(0, 0);
+  // Steps j+1 .. j+AHEAD are in flight while step j is computed.  A buffer is refilled only after the
+  // barrier that ends the step which read it; the wait before that barrier leaves the younger
+  // fetches in flight (loads complete in order).
+#pragma unroll
+  for (int j = 0; j < AHEAD; ++j)
+    if (j < n_steps) fetch(j);
   fetch_landed();
   __syncthreads();
-  for (int st = 0; st < n_stages; ++st) {
-    // start the fetch of the next stage into the other buffer, run this stage's (up to) two steps,
-    // close a chunk if one ends here, and meet the other waves once the fetch has landed
-    const int buf = st & 1;
-    if (st + 1 < n_stages) fetch(st + 1, buf ^ 1);
-#pragma nounroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      const int k0 = k_lo + st * STAGE + s2 * STEP;
-      if (k0 >= k_hi) break;                                  // workgroup-uniform
-      const uint4* sk = &lds_k[buf][s2 * 4 * TV4];
-      const uint16_t* sv = (const uint16_t*)&lds_v[buf][s2 * 4 * TV4];
+  for (int j = 0; j < n_steps; ++j) {
+    if (j + AHEAD < n_steps) fetch(j + AHEAD);                // into the buffer of step j - 1
+    {
+      const int k0 = k_lo + j * STEP;
+      const uint4* sk = &lds_k[j & (NBUF - 1)][0];
+      const uint16_t* sv = (const uint16_t*)&lds_v[j & (NBUF - 1)][0];
       if (k0 + STEP - 1 <= wmin) step(std::false_type{}, sk, sv, k0);    // wave-uniform
       else step(std::true_type{}, sk, sv, k0);
     }
-    if (SUPER && ((st & 1) || st + 1 == n_stages)) {
+    if (SUPER && ((j & 3) == 3 || j + 1 == n_steps)) {
       // a chunk is complete: fold it into the running super partial and start the next one afresh
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
-        if (st < 2) {
+        if (j < 4) {
           sm[cb] = m[cb];
           sl[cb] = l[cb];
 #pragma unroll
@@ -336,7 +349,11 @@ __global__ __launch_bounds__(256) void attention_kernel(
         for (int d = 0; d < DB; ++d) acc[cb][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
     }
-    fetch_landed();
+    // step j + 1 has landed once at most the fetches issued after it are outstanding
+    const int younger = min(j + AHEAD, n_steps - 1) - (j + 1);
+    if (younger >= 2) fetch_wait<2 * FI>();
+    else if (younger == 1) fetch_wait<FI>();
+    else fetch_wait<0>();
     __syncthreads();
   }
 
@@ -418,14 +435,14 @@ __global__ void attention_merge_kernel(const float* __restrict__ part_acc, const
   *dst = o;
 }
 
-template <int HD, int CB, bool SUPER>
+template <int HD, int CB, int NW, bool SUPER>
 void launch_one(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
                 int window, const Workspace& ws, hipStream_t st) {
   const llm42_config& c = m->cfg;
   const float scale_log2 = (1.0f / sqrtf((float)c.head_dim)) * 1.44269504088896340736f;
   const int col_blocks = ws.r_pad / 16;
-  const dim3 grid(ws.attn_units, (col_blocks + 4 * CB - 1) / (4 * CB), num_seqs * c.n_kv_heads);
-  attention_kernel<HD, CB, SUPER><<<grid, 256, 0, st>>>(ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table,
+  const dim3 grid(ws.attn_units, (col_blocks + NW * CB - 1) / (NW * CB), num_seqs * c.n_kv_heads);
+  attention_kernel<HD, CB, NW, SUPER><<<grid, NW * 64, 0, st>>>(ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table,
                                                         ws.seq_len, ws.seq_n, c.n_kv_heads, m->group, window, ws.r_pad,
                                                         kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc,
                                                         ws.part_ml);
@@ -438,13 +455,15 @@ void launch_one(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, co
 template <int HD>
 void launch_hd(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
                int window, const Workspace& ws, hipStream_t st) {
-  const bool two = ws.r_pad / 16 >= 8;
+  // 8 row blocks or more per (sequence, kv head): 8 waves of one row block each, two per SIMD, so
+  // that one wave's MFMAs run under the other's softmax arithmetic; fewer: 4 waves.
+  const bool wide = ws.r_pad / 16 >= 8;
   if (ws.attn_super) {
-    if (two) launch_one<HD, 2, true>(m, kp, vp, kv, num_seqs, window, ws, st);
-    else launch_one<HD, 1, true>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_one<HD, 1, 8, true>(m, kp, vp, kv, num_seqs, window, ws, st);
+    else launch_one<HD, 1, 4, true>(m, kp, vp, kv, num_seqs, window, ws, st);
   } else {
-    if (two) launch_one<HD, 2, false>(m, kp, vp, kv, num_seqs, window, ws, st);
-    else launch_one<HD, 1, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_one<HD, 1, 8, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    else launch_one<HD, 1, 4, false>(m, kp, vp, kv, num_seqs, window, ws, st);
   }
 }
 
