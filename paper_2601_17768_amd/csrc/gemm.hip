@@ -399,16 +399,30 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
 // per XCD and served from that XCD's L2 to the other token tiles.
 // Accumulation order per output element: k ascending inside [k_begin, k_begin + k_count), exactly
 // as in the small-batch kernels; with ADD_PARTIAL the other half's fp32 partial is added at the end.
+// 1 KiB from global memory (wave-uniform `base` + per-lane byte offset `voff`) straight into LDS at
+// byte address `dst` + 16 * lane (M0 holds the wave-uniform destination).  Written as assembly on
+// purpose: with the compiler's own form of this load every later LDS read waits for all earlier
+// ones, which un-pipelines the operand reads.  The compiler therefore does not count these loads;
+// lds_fetch_wait() is the only wait that covers them.  Nothing else in these kernels uses M0.
+__device__ __forceinline__ void lds_fetch_1k(const void* base, uint32_t voff, uint32_t dst) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(dst) : "memory");
+}
+// At most N of the fetches this wave has issued are still on their way (they complete in order).
+template <int N>
+__device__ __forceinline__ void lds_fetch_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 template <int WB, bool ADD_PARTIAL, class Epi>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
                                                          const float* __restrict__ partial, int n, int tiles_n,
                                                          int tiles_m, Epi epi) {
   constexpr int TB = 2 * WB;                 // 16-row blocks per tile side
-  constexpr int KS = 2;                      // k-tiles per stage
-  constexpr int ST = 2 * TB * KS;            // operand tiles per stage (weights then activations)
-  constexpr int PW = ST / 4;                 // operand tiles each wave copies per stage
-  __shared__ bf16x8 lds[2][ST * 64];
+  constexpr int ST = 2 * TB;                 // operand tiles per stage of one k-tile (weights then activations)
+  constexpr int PW = ST / 4;                 // operand tiles each wave fetches per stage
+  constexpr int NST = 4, AHEAD = 3;          // ring of stages in LDS; stages in flight ahead of the one computed
+  __shared__ bf16x8 lds[NST][ST * 64];
   // wave index as a scalar, so that everything derived from it (operand addresses) stays in SGPRs
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wn = wave >> 1, wm = wave & 1;
@@ -425,82 +439,68 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   if (tn >= tiles_n || tm >= tiles_m) return;
   const int n0 = tn * TB, m0 = tm * TB;      // first feature / token block of the tile
 
-  // source of the PW operand tiles this wave copies in every stage (k-tile added per stage)
+  // Operand tiles go from global memory straight into LDS (no staging registers, no LDS stores):
+  // per stage this wave moves PW tiles of 1 KiB, lane i's 16 bytes landing at tile base + 16 i.
+  // src[i] is the wave-uniform start of the i-th tile's row block (k-tile k_begin).
   const bf16x8* src[PW];
-  int kk_of[PW];
 #pragma unroll
   for (int i = 0; i < PW; ++i) {
     const int q = wave * PW + i;                       // 0 .. ST-1
-    const bool is_w = q < TB * KS;
-    const int blk = (is_w ? q : q - TB * KS) / KS;
-    kk_of[i] = q % KS;
+    const bool is_w = q < TB;
+    const int blk = is_w ? q : q - TB;
     const int gb = is_w ? min(n0 + blk, n_blocks - 1) : m0 + blk;   // feature blocks past the matrix re-read the last one
-    src[i] = (is_w ? w : x) + ((size_t)gb * k_tiles + k_begin) * 64 + lane;
+    src[i] = (is_w ? w : x) + ((size_t)gb * k_tiles + k_begin) * 64;
   }
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&lds[0][0];
+  auto fetch = [&](int s) {
+    const uint32_t voff = (uint32_t)s * 1024u + (uint32_t)lane * 16u;
+#pragma unroll
+    for (int i = 0; i < PW; ++i)
+      lds_fetch_1k(src[i], voff, lds_addr + (uint32_t)(((s & (NST - 1)) * ST + wave * PW + i) * 1024));
+  };
   f32x4 acc[WB][WB];
 #pragma unroll
   for (int i = 0; i < WB; ++i)
 #pragma unroll
     for (int j = 0; j < WB; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int stages = (k_count + KS - 1) / KS;
-  // (Native vector types on purpose: register arrays of HIP_vector_type structs end up in scratch.)
-  // (Native vector types on purpose: register arrays of HIP_vector_type structs end up in scratch.
-  // A second staging set - two stages in flight - does not fit next to 256 accumulators: it spills.)
-  bf16x8 stg[PW];
-  auto fetch = [&](int s) {      // k-tiles past the range re-read the last one (never used)
-#pragma unroll
-    for (int i = 0; i < PW; ++i) stg[i] = src[i][(size_t)min(s * KS + kk_of[i], k_count - 1) * 64];
-  };
-  auto park = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < PW; ++i) lds[buf][(wave * PW + i) * 64 + lane] = stg[i];
-  };
-  // A full stage (KS k-tiles), software pipelined by hand: the activation operand needed three
-  // groups of WB MFMAs later and one weight operand of the next k-tile are requested from LDS BEFORE the
-  // current group is issued (the scheduling barriers keep the compiler from sinking the reads next to their
-  // uses, which would leave the MFMA pipe idle for an LDS latency after every group).
+  // One stage (one k-tile), software pipelined by hand: the activation operand needed PD groups of
+  // WB MFMAs later is requested from LDS BEFORE the current group is issued (the scheduling barriers
+  // keep the compiler from sinking the reads next to their uses, which would leave the MFMA pipe idle
+  // for an LDS latency after every group).
   auto compute = [&](int s) {
-    const int buf = s & 1;
-    constexpr int PD = 3;                  // groups of WB MFMAs between an activation operand's request and its use
-    bf16x8 a[2][WB], bq[PD + 1];
+    const bf16x8* st = lds[s & (NST - 1)];
+    constexpr int PD = 3;
+    bf16x8 a[WB], bq[PD + 1];
 #pragma unroll
-    for (int i = 0; i < WB; ++i) a[0][i] = lds[buf][((wn * WB + i) * KS) * 64 + lane];
+    for (int i = 0; i < WB; ++i) a[i] = st[(wn * WB + i) * 64 + lane];
 #pragma unroll
-    for (int t = 0; t < PD; ++t) bq[t] = lds[buf][((TB + wm * WB + t % WB) * KS + t / WB) * 64 + lane];
-#pragma unroll
-    for (int t = 0; t < KS * WB; ++t) {
-      const int kk = t / WB, j = t % WB;
-      if (t + PD < KS * WB) {
-        const int kn = (t + PD) / WB, jn = (t + PD) % WB;
-        bq[(t + PD) % (PD + 1)] = lds[buf][((TB + wm * WB + jn) * KS + kn) * 64 + lane];
-      }
-      if (kk + 1 < KS) a[(kk + 1) & 1][j] = lds[buf][((wn * WB + j) * KS + kk + 1) * 64 + lane];
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < WB; ++i) acc[i][j] = mfma16(a[kk & 1][i], bq[t % (PD + 1)], acc[i][j]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  const int full = k_count / KS;           // full stages; an odd k_count leaves one k-tile for the tail
-  fetch(0);
-  park(0);
-  __syncthreads();
-  for (int s = 0; s < full; ++s) {
-    if (s + 1 < stages) fetch(s + 1);
-    compute(s);
-    if (s + 1 < stages) park((s + 1) & 1);
-    __syncthreads();
-  }
-  if (full < stages) {                     // tail stage holding a single k-tile (kk = 0)
-    const int buf = full & 1;
+    for (int t = 0; t < PD; ++t) bq[t] = st[(TB + wm * WB + t) * 64 + lane];
 #pragma unroll
     for (int j = 0; j < WB; ++j) {
-      const bf16x8 b = lds[buf][((TB + wm * WB + j) * KS) * 64 + lane];
+      if (j + PD < WB) bq[(j + PD) % (PD + 1)] = st[(TB + wm * WB + j + PD) * 64 + lane];
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < WB; ++i)
-        acc[i][j] = mfma16(lds[buf][((wn * WB + i) * KS) * 64 + lane], b, acc[i][j]);
+      for (int i = 0; i < WB; ++i) acc[i][j] = mfma16(a[i], bq[j % (PD + 1)], acc[i][j]);
+      __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  // Stages s+1 .. s+AHEAD are in flight while stage s is computed.  A ring slot is refilled only
+  // after the barrier that ends the stage which read it; the wait before that barrier leaves the
+  // younger fetches in flight (loads complete in order).
+#pragma unroll
+  for (int s = 0; s < AHEAD; ++s)
+    if (s < k_count) fetch(s);
+  lds_fetch_wait<0>();
+  __syncthreads();
+  for (int s = 0; s < k_count; ++s) {
+    if (s + AHEAD < k_count) fetch(s + AHEAD);          // into the slot of stage s - 1
+    compute(s);
+    const int younger = min(s + AHEAD, k_count - 1) - (s + 1);
+    if (younger >= 2) lds_fetch_wait<2 * PW>();
+    else if (younger == 1) lds_fetch_wait<PW>();
+    else lds_fetch_wait<0>();
+    __syncthreads();
   }
   // epilogue, token block by token block: what depends on the token row only is fetched once per row
 #pragma unroll
