@@ -8,6 +8,8 @@
 // depends on K only.  How many token blocks a wave owns, how many waves share a
 // workgroup and how the grid is shaped are work-distribution choices that do not
 // touch it, so they may change with the number of rows.
+#include <type_traits>
+
 #include "llm42_dev.h"
 
 namespace {
@@ -407,6 +409,16 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
 __device__ __forceinline__ void lds_fetch_1k(const void* base, uint32_t voff, uint32_t dst) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(dst) : "memory");
 }
+// acc += a * b with the accumulator pinned to the same four accumulation registers before and after.
+// (Left to the compiler, some instantiations of the tiled kernel compute into a temporary and copy
+// it back - four moves behind every MFMA of the main loop.)  The compiler does not know that this is
+// an MFMA: the kernel leaves idle cycles between its last MFMA and the first read of an accumulator
+// (mfma_drain), and never issues two of these on the same accumulator back to back.
+__device__ __forceinline__ void mfma16_inplace(const bf16x8 a, const bf16x8 b, f32x4& acc) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 // At most N of the fetches this wave has issued are still on their way (they complete in order).
 template <int N>
 __device__ __forceinline__ void lds_fetch_wait() {
@@ -421,7 +433,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   constexpr int TB = 2 * WB;                 // 16-row blocks per tile side
   constexpr int ST = 2 * TB;                 // operand tiles per stage of one k-tile (weights then activations)
   constexpr int PW = ST / 4;                 // operand tiles each wave fetches per stage
-  constexpr int NST = 4, AHEAD = 3;          // ring of stages in LDS; stages in flight ahead of the one computed
+  constexpr int NST = 4;                     // ring of stages in LDS
   __shared__ bf16x8 lds[NST][ST * 64];
   // wave index as a scalar, so that everything derived from it (operand addresses) stays in SGPRs
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -452,8 +464,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
     src[i] = (is_w ? w : x) + ((size_t)gb * k_tiles + k_begin) * 64;
   }
   const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&lds[0][0];
-  auto fetch = [&](int s) {
-    const uint32_t voff = (uint32_t)s * 1024u + (uint32_t)lane * 16u;
+  auto fetch = [&](int s) {      // k-tiles past the range re-read the last one
+    const uint32_t voff = (uint32_t)min(s, k_count - 1) * 1024u + (uint32_t)lane * 16u;
 #pragma unroll
     for (int i = 0; i < PW; ++i)
       lds_fetch_1k(src[i], voff, lds_addr + (uint32_t)(((s & (NST - 1)) * ST + wave * PW + i) * 1024));
@@ -464,44 +476,50 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
 #pragma unroll
     for (int j = 0; j < WB; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // One stage (one k-tile), software pipelined by hand: the activation operand needed PD groups of
-  // WB MFMAs later is requested from LDS BEFORE the current group is issued (the scheduling barriers
-  // keep the compiler from sinking the reads next to their uses, which would leave the MFMA pipe idle
-  // for an LDS latency after every group).
-  auto compute = [&](int s) {
-    const bf16x8* st = lds[s & (NST - 1)];
-    constexpr int PD = 3;
-    bf16x8 a[WB], bq[PD + 1];
+  // One stage = one k-tile = WB groups of WB MFMAs (group j: token block j against the wave's WB
+  // feature blocks).  Software pipelined by hand across stages, so that the MFMA pipe never waits for
+  // LDS or for the barrier: the activation operand of a group is requested from LDS PD groups ahead,
+  // and after group JB - when every read of this stage has been issued - the wave waits for the next
+  // stage's tiles, meets the others, refills the ring slot this stage occupied and requests the next
+  // stage's weight operands, all while the remaining groups of this stage still run.  (The scheduling
+  // barriers keep the compiler from sinking the reads next to their uses.)
+  constexpr int PD = 3, JB = WB - PD;
+  static_assert(WB % (PD + 1) == 0 && JB >= 0, "operand ring must line up across stages");
+  bf16x8 bq[PD + 1];
+  auto w_operands = [&](bf16x8(&dst)[WB], int s) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < WB; ++i) a[i] = st[(wn * WB + i) * 64 + lane];
+    for (int i = 0; i < WB; ++i) dst[i] = lds[s & (NST - 1)][(wn * WB + i) * 64 + lane];
+  };
+  auto x_operand = [&](int s, int j) { return lds[s & (NST - 1)][(TB + wm * WB + j) * 64 + lane]; };
+  // The loop body is kept free of branches (the register allocation of 256 accumulators does not
+  // survive control flow inside it): every stage issues a fetch and waits with the same count.  Past
+  // the end of the k range the fetches re-read the last k-tile into ring slots that nothing reads.
 #pragma unroll
-    for (int t = 0; t < PD; ++t) bq[t] = st[(TB + wm * WB + t) * 64 + lane];
+  for (int s = 0; s < NST; ++s) fetch(s);
+  lds_fetch_wait<(NST - 1) * PW>();                    // stage 0 has landed
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < PD; ++t) bq[t] = x_operand(0, t);
+  for (int s = 0; s < k_count; ++s) {
+    bf16x8 a[WB];
+    w_operands(a, s);
 #pragma unroll
     for (int j = 0; j < WB; ++j) {
-      if (j + PD < WB) bq[(j + PD) % (PD + 1)] = st[(TB + wm * WB + j + PD) * 64 + lane];
+      if (j == JB) {
+        lds_fetch_wait<(NST - 2) * PW>();              // stage s + 1 has landed: only the two after it may be outstanding
+        __syncthreads();                               // also: every wave has read all it needs of stage s
+        fetch(s + NST);                                // into the slot of stage s
+      }
+      // (in the last stage the operands requested for a following stage are stale tiles that nothing consumes)
+      bq[(j + PD) % (PD + 1)] = j + PD < WB ? x_operand(s, j + PD) : x_operand(s + 1, j + PD - WB);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < WB; ++i) acc[i][j] = mfma16(a[i], bq[j % (PD + 1)], acc[i][j]);
+      for (int i = 0; i < WB; ++i) mfma16_inplace(a[i], bq[j % (PD + 1)], acc[i][j]);
       __builtin_amdgcn_sched_barrier(0);
     }
-  };
-  // Stages s+1 .. s+AHEAD are in flight while stage s is computed.  A ring slot is refilled only
-  // after the barrier that ends the stage which read it; the wait before that barrier leaves the
-  // younger fetches in flight (loads complete in order).
-#pragma unroll
-  for (int s = 0; s < AHEAD; ++s)
-    if (s < k_count) fetch(s);
-  lds_fetch_wait<0>();
-  __syncthreads();
-  for (int s = 0; s < k_count; ++s) {
-    if (s + AHEAD < k_count) fetch(s + AHEAD);          // into the slot of stage s - 1
-    compute(s);
-    const int younger = min(s + AHEAD, k_count - 1) - (s + 1);
-    if (younger >= 2) lds_fetch_wait<2 * PW>();
-    else if (younger == 1) lds_fetch_wait<PW>();
-    else lds_fetch_wait<0>();
-    __syncthreads();
   }
+  lds_fetch_wait<0>();
+  mfma_drain();
   // epilogue, token block by token block: what depends on the token row only is fetched once per row
 #pragma unroll
   for (int j = 0; j < WB; ++j) {
