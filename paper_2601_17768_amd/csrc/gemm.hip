@@ -500,23 +500,32 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   __syncthreads();
 #pragma unroll
   for (int t = 0; t < PD; ++t) bq[t] = x_operand(0, t);
-  for (int s = 0; s < k_count; ++s) {
-    bf16x8 a[WB];
-    w_operands(a, s);
+  bf16x8 a[2][WB];
+  w_operands(a[0], 0);
+  auto stage = [&](int s, const bf16x8(&cur)[WB], bf16x8(&next)[WB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < WB; ++j) {
       if (j == JB) {
         lds_fetch_wait<(NST - 2) * PW>();              // stage s + 1 has landed: only the two after it may be outstanding
         __syncthreads();                               // also: every wave has read all it needs of stage s
         fetch(s + NST);                                // into the slot of stage s
+        w_operands(next, s + 1);                       // weight operands of the next stage, while this one finishes
       }
       // (in the last stage the operands requested for a following stage are stale tiles that nothing consumes)
       bq[(j + PD) % (PD + 1)] = j + PD < WB ? x_operand(s, j + PD) : x_operand(s + 1, j + PD - WB);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < WB; ++i) mfma16_inplace(a[i], bq[j % (PD + 1)], acc[i][j]);
+      for (int i = 0; i < WB; ++i) mfma16_inplace(cur[i], bq[j % (PD + 1)], acc[i][j]);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  {
+    int s = 0;
+    for (; s + 1 < k_count; s += 2) {
+      stage(s, a[0], a[1]);
+      stage(s + 1, a[1], a[0]);
+    }
+    if (s < k_count) stage(s, a[0], a[1]);
   }
   lds_fetch_wait<0>();
   mfma_drain();
