@@ -390,15 +390,16 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
 }
 
 // Large-batch kernel (more than 64 tokens): MFMA-bound, LDS-tiled.  A workgroup of 4 waves (2 x 2)
-// owns a tile of 32*WB features x 32*WB tokens (WB = 8: 256 x 256, WB = 4: 128 x 128); each wave owns
-// WB x WB MFMA blocks (WB*WB*4 accumulator registers).  Per stage of KS = 2 k-tiles the four waves
-// copy the tile's 2*TB*KS operand tiles (1 KiB each, already in MFMA operand order) from global
-// memory to LDS through registers - the loads of stage s+1 are issued before stage s is computed
-// and parked after it, one barrier per stage, LDS double buffered - and every wave reads its WB
-// weight operands and WB activation operands per k-tile with conflict-free 16-byte LDS reads.
-// Workgroups are numbered so that the workgroups that land on one XCD (id mod 8) walk through
-// consecutive token tiles of the same feature tile: the weight tile is then fetched from HBM once
-// per XCD and served from that XCD's L2 to the other token tiles.
+// owns a tile of 32*WBN features x 32*WBM tokens; each wave owns WBN x WBM MFMA blocks (WBN*WBM*4
+// accumulator registers).  Per stage of one k-tile the four waves move the tile's 2*(WBN+WBM) operand
+// tiles (1 KiB each, already in MFMA operand order) from global memory straight into a ring of NST
+// stages in LDS; every wave reads its WBN weight operands and WBM activation operands per k-tile
+// with conflict-free 16-byte LDS reads.  WGS workgroups share a CU: one wave per SIMD cannot keep
+// the MFMA pipe busy by itself (an MFMA loop on registers alone reaches 58 % of peak with one wave
+// per SIMD and 89 % with two), so the shipped shape is 128 x 256 with two workgroups per CU.
+// Workgroups are numbered so that the workgroups that land on one XCD (id mod 8) form a super-tile
+// of 4 x 8 tiles: weight and activation tiles are then fetched from HBM once per XCD and served
+// from that XCD's L2 to the rest of the super-tile.
 // Accumulation order per output element: k ascending inside [k_begin, k_begin + k_count), exactly
 // as in the small-batch kernels; with ADD_PARTIAL the other half's fp32 partial is added at the end.
 // 1 KiB from global memory (wave-uniform `base` + per-lane byte offset `voff`) straight into LDS at
@@ -425,15 +426,16 @@ __device__ __forceinline__ void lds_fetch_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int WB, bool ADD_PARTIAL, class Epi>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
+template <int WBN, int WBM, int NST, int WGS, bool ADD_PARTIAL, class Epi>
+__global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
                                                          const float* __restrict__ partial, int n, int tiles_n,
                                                          int tiles_m, Epi epi) {
-  constexpr int TB = 2 * WB;                 // 16-row blocks per tile side
-  constexpr int ST = 2 * TB;                 // operand tiles per stage of one k-tile (weights then activations)
-  constexpr int PW = ST / 4;                 // operand tiles each wave fetches per stage
-  constexpr int NST = 4;                     // ring of stages in LDS
+  constexpr int TBN = 2 * WBN, TBM = 2 * WBM;   // 16-row blocks per tile side (features, tokens)
+  constexpr int ST = TBN + TBM;                 // operand tiles per stage of one k-tile (weights then activations)
+  constexpr int PW = ST / 4;                    // operand tiles each wave fetches per stage
+  static_assert(ST % 4 == 0, "a stage's tiles are dealt evenly to the four waves");
+  // NST = ring of stages in LDS
   __shared__ bf16x8 lds[NST][ST * 64];
   // wave index as a scalar, so that everything derived from it (operand addresses) stays in SGPRs
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -449,7 +451,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   if (sup >= sup_n * sup_m) return;
   const int tn = (sup / sup_m) * SN + in_sup / SM, tm = (sup % sup_m) * SM + in_sup % SM;
   if (tn >= tiles_n || tm >= tiles_m) return;
-  const int n0 = tn * TB, m0 = tm * TB;      // first feature / token block of the tile
+  const int n0 = tn * TBN, m0 = tm * TBM;      // first feature / token block of the tile
 
   // Operand tiles go from global memory straight into LDS (no staging registers, no LDS stores):
   // per stage this wave moves PW tiles of 1 KiB, lane i's 16 bytes landing at tile base + 16 i.
@@ -458,8 +460,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
 #pragma unroll
   for (int i = 0; i < PW; ++i) {
     const int q = wave * PW + i;                       // 0 .. ST-1
-    const bool is_w = q < TB;
-    const int blk = is_w ? q : q - TB;
+    const bool is_w = q < TBN;
+    const int blk = is_w ? q : q - TBN;
     const int gb = is_w ? min(n0 + blk, n_blocks - 1) : m0 + blk;   // feature blocks past the matrix re-read the last one
     src[i] = (is_w ? w : x) + ((size_t)gb * k_tiles + k_begin) * 64;
   }
@@ -468,29 +470,29 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
     const uint32_t voff = (uint32_t)min(s, k_count - 1) * 1024u + (uint32_t)lane * 16u;
 #pragma unroll
     for (int i = 0; i < PW; ++i)
-      lds_fetch_1k(src[i], voff, lds_addr + (uint32_t)(((s & (NST - 1)) * ST + wave * PW + i) * 1024));
+      lds_fetch_1k(src[i], voff, lds_addr + (uint32_t)(((s % NST) * ST + wave * PW + i) * 1024));
   };
-  f32x4 acc[WB][WB];
+  f32x4 acc[WBN][WBM];
 #pragma unroll
-  for (int i = 0; i < WB; ++i)
+  for (int i = 0; i < WBN; ++i)
 #pragma unroll
-    for (int j = 0; j < WB; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < WBM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // One stage = one k-tile = WB groups of WB MFMAs (group j: token block j against the wave's WB
+  // One stage = one k-tile = WBM groups of WBN MFMAs (group j: token block j against the wave's WBN
   // feature blocks).  Software pipelined by hand across stages, so that the MFMA pipe never waits for
   // LDS or for the barrier: the activation operand of a group is requested from LDS PD groups ahead,
   // and after group JB - when every read of this stage has been issued - the wave waits for the next
   // stage's tiles, meets the others, refills the ring slot this stage occupied and requests the next
   // stage's weight operands, all while the remaining groups of this stage still run.  (The scheduling
   // barriers keep the compiler from sinking the reads next to their uses.)
-  constexpr int PD = 3, JB = WB - PD;
-  static_assert(WB % (PD + 1) == 0 && JB >= 0, "operand ring must line up across stages");
+  constexpr int PD = 3, JB = WBM - PD;
+  static_assert(WBM % (PD + 1) == 0 && JB >= 0, "operand ring must line up across stages");
   bf16x8 bq[PD + 1];
-  auto w_operands = [&](bf16x8(&dst)[WB], int s) __attribute__((always_inline)) {
+  auto w_operands = [&](bf16x8(&dst)[WBN], int s) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < WB; ++i) dst[i] = lds[s & (NST - 1)][(wn * WB + i) * 64 + lane];
+    for (int i = 0; i < WBN; ++i) dst[i] = lds[s % NST][(wn * WBN + i) * 64 + lane];
   };
-  auto x_operand = [&](int s, int j) { return lds[s & (NST - 1)][(TB + wm * WB + j) * 64 + lane]; };
+  auto x_operand = [&](int s, int j) { return lds[s % NST][(TBN + wm * WBM + j) * 64 + lane]; };
   // The loop body is kept free of branches (the register allocation of 256 accumulators does not
   // survive control flow inside it): every stage issues a fetch and waits with the same count.  Past
   // the end of the k range the fetches re-read the last k-tile into ring slots that nothing reads.
@@ -500,11 +502,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   __syncthreads();
 #pragma unroll
   for (int t = 0; t < PD; ++t) bq[t] = x_operand(0, t);
-  bf16x8 a[2][WB];
+  bf16x8 a[2][WBN];
   w_operands(a[0], 0);
-  auto stage = [&](int s, const bf16x8(&cur)[WB], bf16x8(&next)[WB]) __attribute__((always_inline)) {
+  auto stage = [&](int s, const bf16x8(&cur)[WBN], bf16x8(&next)[WBN]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < WB; ++j) {
+    for (int j = 0; j < WBM; ++j) {
       if (j == JB) {
         lds_fetch_wait<(NST - 2) * PW>();              // stage s + 1 has landed: only the two after it may be outstanding
         __syncthreads();                               // also: every wave has read all it needs of stage s
@@ -512,10 +514,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
         w_operands(next, s + 1);                       // weight operands of the next stage, while this one finishes
       }
       // (in the last stage the operands requested for a following stage are stale tiles that nothing consumes)
-      bq[(j + PD) % (PD + 1)] = j + PD < WB ? x_operand(s, j + PD) : x_operand(s + 1, j + PD - WB);
+      bq[(j + PD) % (PD + 1)] = j + PD < WBM ? x_operand(s, j + PD) : x_operand(s + 1, j + PD - WBM);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < WB; ++i) mfma16_inplace(cur[i], bq[j % (PD + 1)], acc[i][j]);
+      for (int i = 0; i < WBN; ++i) mfma16_inplace(cur[i], bq[j % (PD + 1)], acc[i][j]);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -531,12 +533,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   mfma_drain();
   // epilogue, token block by token block: what depends on the token row only is fetched once per row
 #pragma unroll
-  for (int j = 0; j < WB; ++j) {
-    const int row = (m0 + wm * WB + j) * 16 + (lane & 15);
+  for (int j = 0; j < WBM; ++j) {
+    const int row = (m0 + wm * WBM + j) * 16 + (lane & 15);
     const typename Epi::Row ri = epi.row_info(row);
 #pragma unroll
-    for (int i = 0; i < WB; ++i) {
-      const int nb = n0 + wn * WB + i;
+    for (int i = 0; i < WBN; ++i) {
+      const int nb = n0 + wn * WBN + i;
       if (nb < n_blocks) {
         f32x4 v = acc[i][j];
         if (ADD_PARTIAL) v = v + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
@@ -546,25 +548,28 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const bf16x8* __restric
   }
 }
 
-template <int WB, int SPLIT, class Epi>
+template <int WBN, int WBM, int NST, int WGS, int SPLIT, class Epi>
 void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles, int n, const Workspace& ws,
                   const Epi& epi, hipStream_t st) {
-  const int tb = 2 * WB, tiles_n = (n_blocks + tb - 1) / tb, tiles_m = ws.m_pad / (16 * tb);
+  const int tiles_n = (n_blocks + 2 * WBN - 1) / (2 * WBN), tiles_m = ws.m_pad / (32 * WBM);
   const int supers = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);      // super-tiles of 4 x 8 tiles, 8 XCDs
   const unsigned grid = 8u * 32u * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
-    gemm_tiled_kernel<WB, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr, n, tiles_n,
-                                                            tiles_m, epi);
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr,
+                                                                            n, tiles_n, tiles_m, epi);
   } else {
     const int h = split_point(k_tiles);
     StorePartialEpi pe{ws.split_part, n};
-    gemm_tiled_kernel<WB, false, StorePartialEpi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, h, k_tiles - h,
-                                                                        nullptr, n, tiles_n, tiles_m, pe);
-    gemm_tiled_kernel<WB, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part, n, tiles_n,
-                                                           tiles_m, epi);
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi><<<grid, 256, 0, st>>>(
+        wp, xp, n_blocks, k_tiles, h, k_tiles - h, nullptr, n, tiles_n, tiles_m, pe);
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part,
+                                                                           n, tiles_n, tiles_m, epi);
   }
 }
 
+#ifndef LLM42_TILE_BIG
+#define LLM42_TILE_BIG 4, 8, 3, 2
+#endif
 enum GemmKind { GEMM_QKV = 0, GEMM_RESIDUAL = 1, GEMM_GATE_UP = 2, GEMM_LOGITS = 3 };
 // The split of each GEMM type (part of the reduction schedule, see above).
 constexpr int kSplit[4] = {1, 2, 1, 1};
@@ -598,8 +603,8 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
     return;
   }
   // more than 64 tokens: m_pad is a multiple of 128 (up to 512 rows) or of 256 (beyond)
-  if (m_pad >= 512 && m_pad % 256 == 0) launch_tiled<8, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
-  else launch_tiled<4, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  if (m_pad >= 512 && m_pad % 256 == 0) launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  else launch_tiled<4, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
 }
 
 }  // namespace
