@@ -174,46 +174,7 @@ struct LogitsEpi {
 // ---------------------------------------------------------------------------------------------
 __host__ __device__ inline int split_point(int k_tiles) { return (k_tiles + 1) / 2; }
 
-// Large-batch fallback: every wave owns one block of 16 features and MB blocks of 16 tokens and
-// walks k-tiles [k_begin, k_begin + k_count).  With ADD_PARTIAL the fp32 partial of the other
-// half (stored earlier by the same kernel with a StorePartialEpi) is added before the epilogue.
-template <int MB, bool ADD_PARTIAL, class Epi>
-__global__ __launch_bounds__(256) void gemm_stream_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
-                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
-                                                          const float* __restrict__ partial, int n, Epi epi) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nb = blockIdx.x * 4 + wave;
-  if (nb >= n_blocks) return;
-  const int mb0 = blockIdx.y * MB;
-  const bf16x8* wp = w + ((size_t)nb * k_tiles + k_begin) * 64 + lane;
-  const bf16x8* xp = x + ((size_t)mb0 * k_tiles + k_begin) * 64 + lane;
-  f32x4 acc[MB];
-#pragma unroll
-  for (int b = 0; b < MB; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  constexpr int U = 8;
-  int kt = 0;
-  for (; kt + U <= k_count; kt += U) {
-    bf16x8 a[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(wp + (size_t)(kt + u) * 64);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int b = 0; b < MB; ++b) acc[b] = mfma16(a[u], xp[((size_t)b * k_tiles + kt + u) * 64], acc[b]);
-  }
-  for (; kt < k_count; ++kt) {
-    const bf16x8 a = __builtin_nontemporal_load(wp + (size_t)kt * 64);
-#pragma unroll
-    for (int b = 0; b < MB; ++b) acc[b] = mfma16(a, xp[((size_t)b * k_tiles + kt) * 64], acc[b]);
-  }
-#pragma unroll
-  for (int b = 0; b < MB; ++b) {
-    const int row = (mb0 + b) * 16 + (lane & 15);
-    if (ADD_PARTIAL) acc[b] = acc[b] + *(const f32x4*)(partial + resid_off(row, nb * 16 + (lane >> 4) * 4, n));
-    epi(nb, lane, row, acc[b], epi.pre(nb, lane, row, epi.row_info(row)));
-  }
-}
-
+// fp32 partial of one k-half of a split GEMM (large-batch path: the halves are two launches).
 struct StorePartialEpi {
   float* partial;   // [m_pad][n] in the residual-stream layout
   int n;

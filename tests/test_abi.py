@@ -77,5 +77,5 @@ def test_kv_layout_round_trip():
     tile_v = kv[layer, 1, ids[pos // 16], head]
     t = pos % 16
     assert tile_k[((f // 8) * 16 + t) * 8 + f % 8] == k[layer, pos, head, f]
-    assert tile_v[f * 16 + t] == v[layer, pos, head, f]
+    assert tile_v[(((f // 16) * 4 + t // 4) * 16 + f % 16) * 4 + t % 4] == v[layer, pos, head, f]
     assert bool((kv[:, :, [0, 1, 3, 4]] == 0).all())        # other blocks untouched
