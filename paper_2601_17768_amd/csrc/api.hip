@@ -105,6 +105,8 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   const size_t part_rows = (size_t)num_seqs * c.n_kv_heads * ws.attn_units * ws.r_pad;
   ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
   ws.part_ml = (float*)take(8ull * part_rows);
+  ws.attn_items = (int2*)take(sizeof(int2) * (size_t)num_seqs * ws.attn_units);
+  ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (1 + c.n_layers));
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
   ws.split_part = (float*)take(ws.m_pad > 64 ? 4ull * ws.m_pad * c.d_model : 0);
   ws.bytes = off;
@@ -137,6 +139,15 @@ llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w,
 
   llm42_model* m = new llm42_model();
   m->cfg = c;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+      delete m;
+      return fail(LLM42_EHIP, "model_create: cannot query the device");
+    }
+    m->num_cus = cus;
+  }
   m->group = c.n_q_heads / c.n_kv_heads;
   m->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
   m->d_attn = c.n_q_heads * c.head_dim;
@@ -267,6 +278,7 @@ llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv,
   const llm42_config& c = m->cfg;
   TIMED(LLM42_K_PREPARE, launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context,
                                         dump_seq_ids, n_dump, out_tokens, seq_status, ws, st));
+  TIMED(LLM42_K_PREPARE, launch_attention_plan(m, num_seqs, ws, st));
   TIMED(LLM42_K_EMBED, launch_embed(m, candidates, ws, st));
   for (int l = 0; l < c.n_layers; ++l) {
     const llm42_model::Layer& ly = m->layers[l];

@@ -26,6 +26,7 @@
 // query rows are ordered r = q_head_in_group * window + i.  K and V tiles are
 // fetched once per workgroup, 128 keys at a time (the next stage's loads are issued
 // before the current stage is computed), double buffered through LDS in MFMA operand order (see the KV tile layouts in llm42.h), so no transpose is needed.
+#include <algorithm>
 #include <type_traits>
 
 #include "llm42_dev.h"
@@ -99,8 +100,9 @@ template <int HD, int CB, int NW, bool SUPER>
 __global__ __launch_bounds__(NW * 64) void attention_kernel(
     const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
-    int n_kv_heads, int group, int window, int r_pad, int max_blocks_per_seq, int n_units, float scale_log2,
-    float* __restrict__ part_acc, float* __restrict__ part_ml) {
+    const int2* __restrict__ items, const int32_t* __restrict__ item_count, int32_t* __restrict__ queue,
+    int n_kv_heads, int group, int window, int r_pad, int y_blocks, int max_blocks_per_seq, int n_units,
+    float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml) {
   constexpr int DK = HD / 32;        // MFMA k-steps over the head dimension (scores)
   constexpr int DB = HD / 16;        // 16-feature blocks of the output
   constexpr int TV4 = HD * 2;        // uint4 per KV tile (16 tokens x HD bf16)
@@ -113,11 +115,16 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
   __shared__ uint4 lds_k[NBUF][4 * TV4];   // per step: 4 K tiles
   __shared__ uint4 lds_v[NBUF][4 * TV4];   // and 4 V tiles
   __shared__ int wg_max[NW];
+  __shared__ int next_work;
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 15, g = lane >> 4;
-  const int unit = blockIdx.x;
-  const int s = blockIdx.z / n_kv_heads, kvh = blockIdx.z % n_kv_heads;
+  const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_k[0][0];
+  const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_v[0][0];
+
+  // One work item: unit `unit` of the keys of sequence `s`, kv head `kvh`, for the `yb`-th group of
+  // NW * CB blocks of 16 query rows.  (A return leaves the item; every condition is workgroup-uniform.)
+  auto run_item = [&](const int unit, const int yb, const int s, const int kvh) {
   const int k_lo = unit * UNIT;
   const int32_t* bt = block_table + (size_t)s * max_blocks_per_seq;
   // Requested before anything is known about the sequence, so that the three latencies (lengths,
@@ -130,7 +137,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
   int row[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
-    row[cb] = ((blockIdx.y * NW + wave) * CB + cb) * 16 + col;
+    row[cb] = ((yb * NW + wave) * CB + cb) * 16 + col;
     // row blocks past r_pad (grid padding) read the last real block instead; their rows are dead anyway
     const int rb = min(row[cb] >> 4, r_pad / 16 - 1);
     const uint16_t* qb = q + ((size_t)s * n_kv_heads + kvh) * r_pad * HD + (size_t)rb * DK * 512;
@@ -172,8 +179,6 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
 
   // each wave fetches one (4 waves) or half (8 waves) of the four blocks of a step, its K and its V
   // tile, straight from global memory into LDS
-  const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_k[0][0];
-  const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(lds_ptr)&lds_v[0][0];
   auto fetch = [&](int j) {
     constexpr int SPLIT = NW / 4, PIECES = TL / SPLIT;       // waves per block; 1 KiB pieces per wave and tile
     const int blk = wave / SPLIT, part = wave % SPLIT;
@@ -367,6 +372,63 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     for (int d = 0; d < DB; ++d) *(f32x4*)(pa + d * 16 + g * 4) = SUPER ? sacc[cb][d] : acc[cb][d];
     if (g == 0) *(float2*)(part_ml + prow * 2) = SUPER ? make_float2(sm[cb], sl[cb]) : make_float2(m[cb], l[cb]);
   }
+  };  // run_item
+
+  // Work distribution: the workgroups of the (CU-sized) grid take one item each to begin with and
+  // pull further ones from a queue.  The list of (sequence, unit) pairs that hold keys is built once
+  // per call (attention_plan_kernel), so no workgroup is spent on a unit past a sequence's end, and
+  // the order in which workgroups finish does not matter: every item writes its own partial.
+  const int per_item = n_kv_heads * y_blocks;
+  const int total = *item_count * per_item;
+  for (int t = blockIdx.x; t < total;) {
+    const int it = t / per_item, rem = t - it * per_item;
+    const int2 su = items[it];
+    run_item(su.y, rem % y_blocks, su.x, rem / y_blocks);
+    __syncthreads();                                       // every wave is done with the ring
+    if (threadIdx.x == 0) next_work = (int)gridDim.x + atomicAdd(queue, 1);
+    __syncthreads();
+    t = next_work;
+  }
+}
+
+// The (sequence, unit) pairs that hold keys, full units first (long items first keeps the tail of
+// the launch short), and the per-layer queue counters.  One workgroup; runs once per call.
+__global__ __launch_bounds__(256) void attention_plan_kernel(const int32_t* __restrict__ seq_len,
+                                                             const int32_t* __restrict__ seq_n, int num_seqs,
+                                                             int unit_keys, int2* __restrict__ items,
+                                                             int32_t* __restrict__ item_count,
+                                                             int32_t* __restrict__ queues, int n_layers) {
+  __shared__ int scan[256];
+  __shared__ int base;
+  if (threadIdx.x == 0) base = 0;
+  for (int l = threadIdx.x; l < n_layers; l += 256) queues[l] = 0;
+  __syncthreads();
+  for (int pass = 0; pass < 2; ++pass) {                   // 0: units fully covered by keys, 1: the last, partial unit
+    for (int s0 = 0; s0 < num_seqs; s0 += 256) {
+      const int s = s0 + threadIdx.x;
+      int first = 0, cnt = 0;
+      if (s < num_seqs && seq_len[s] >= 0) {
+        const int keys = seq_len[s] + seq_n[s];              // positions 0 .. keys-1 are attended to
+        const int full = keys / unit_keys;
+        if (pass == 0) cnt = full;
+        else { first = full; cnt = keys % unit_keys ? 1 : 0; }
+      }
+      scan[threadIdx.x] = cnt;
+      __syncthreads();
+      for (int off = 1; off < 256; off <<= 1) {              // inclusive scan
+        const int v = threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
+        __syncthreads();
+        scan[threadIdx.x] += v;
+        __syncthreads();
+      }
+      const int at = base + scan[threadIdx.x] - cnt;
+      for (int u = 0; u < cnt; ++u) items[at + u] = make_int2(s, first + u);
+      __syncthreads();
+      if (threadIdx.x == 255) base += scan[255];
+      __syncthreads();
+    }
+  }
+  if (threadIdx.x == 0) *item_count = base;
 }
 
 // Fold the partials of every query row (chunks inside a super left to right, then the supers
@@ -436,16 +498,19 @@ __global__ void attention_merge_kernel(const float* __restrict__ part_acc, const
 }
 
 template <int HD, int CB, int NW, bool SUPER>
-void launch_one(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
-                int window, const Workspace& ws, hipStream_t st) {
+void launch_one(const llm42_model* m, int layer, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv,
+                int num_seqs, int window, const Workspace& ws, hipStream_t st) {
   const llm42_config& c = m->cfg;
   const float scale_log2 = (1.0f / sqrtf((float)c.head_dim)) * 1.44269504088896340736f;
   const int col_blocks = ws.r_pad / 16;
-  const dim3 grid(ws.attn_units, (col_blocks + NW * CB - 1) / (NW * CB), num_seqs * c.n_kv_heads);
-  attention_kernel<HD, CB, NW, SUPER><<<grid, NW * 64, 0, st>>>(ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table,
-                                                        ws.seq_len, ws.seq_n, c.n_kv_heads, m->group, window, ws.r_pad,
-                                                        kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc,
-                                                        ws.part_ml);
+  const int y_blocks = (col_blocks + NW * CB - 1) / (NW * CB);
+  // one workgroup per CU (the KV ring takes 128 KiB of LDS at head_dim 128), but no more than there can be items
+  const long long max_items = (long long)num_seqs * ws.attn_units * c.n_kv_heads * y_blocks;
+  const unsigned grid = (unsigned)std::min<long long>(m->num_cus * (HD == 128 ? 1 : 2), max_items);
+  attention_kernel<HD, CB, NW, SUPER><<<grid, NW * 64, 0, st>>>(
+      ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table, ws.seq_len, ws.seq_n, ws.attn_items, ws.attn_ctrl,
+      ws.attn_ctrl + 1 + layer, c.n_kv_heads, m->group, window, ws.r_pad, y_blocks, kv->max_blocks_per_seq,
+      ws.attn_units, scale_log2, ws.part_acc, ws.part_ml);
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
   attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
@@ -453,21 +518,26 @@ void launch_one(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, co
 }
 
 template <int HD>
-void launch_hd(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
-               int window, const Workspace& ws, hipStream_t st) {
+void launch_hd(const llm42_model* m, int layer, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv,
+               int num_seqs, int window, const Workspace& ws, hipStream_t st) {
   // 8 row blocks or more per (sequence, kv head): 8 waves of one row block each, two per SIMD, so
   // that one wave's MFMAs run under the other's softmax arithmetic; fewer: 4 waves.
   const bool wide = ws.r_pad / 16 >= 8;
   if (ws.attn_super) {
-    if (wide) launch_one<HD, 1, 8, true>(m, kp, vp, kv, num_seqs, window, ws, st);
-    else launch_one<HD, 1, 4, true>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_one<HD, 1, 8, true>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
+    else launch_one<HD, 1, 4, true>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   } else {
-    if (wide) launch_one<HD, 1, 8, false>(m, kp, vp, kv, num_seqs, window, ws, st);
-    else launch_one<HD, 1, 4, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_one<HD, 1, 8, false>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
+    else launch_one<HD, 1, 4, false>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   }
 }
 
 }  // namespace
+
+void launch_attention_plan(const llm42_model* m, int num_seqs, const Workspace& ws, hipStream_t st) {
+  attention_plan_kernel<<<1, 256, 0, st>>>(ws.seq_len, ws.seq_n, num_seqs, ws.attn_super ? SUPER_KEYS : CHUNK,
+                                           ws.attn_items, ws.attn_ctrl, ws.attn_ctrl + 1, m->cfg.n_layers);
+}
 
 int attention_units(bool super_mode, int max_context) {
   const int keys = super_mode ? SUPER_KEYS : CHUNK;
@@ -480,6 +550,6 @@ void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv,
   const size_t plane = (size_t)kv->num_blocks * c.n_kv_heads * 16 * c.head_dim;
   const uint16_t* kp = (const uint16_t*)kv->kv_base + ((size_t)layer * 2 + 0) * plane;
   const uint16_t* vp = (const uint16_t*)kv->kv_base + ((size_t)layer * 2 + 1) * plane;
-  if (c.head_dim == 128) launch_hd<128>(m, kp, vp, kv, num_seqs, window, ws, st);
-  else launch_hd<64>(m, kp, vp, kv, num_seqs, window, ws, st);
+  if (c.head_dim == 128) launch_hd<128>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
+  else launch_hd<64>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
 }

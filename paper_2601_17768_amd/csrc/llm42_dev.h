@@ -68,6 +68,7 @@ __device__ inline f32x4 mfma16(const bf16x8 a, const bf16x8 b, const f32x4 c) {
 // ---------------------------------------------------------------------------
 struct llm42_model {
   llm42_config cfg;
+  int num_cus;      // compute units of the device the model lives on
   int group;        // q heads per kv head
   int n_qkv;        // (n_q_heads + 2 n_kv_heads) * head_dim
   int d_attn;       // n_q_heads * head_dim
@@ -95,6 +96,8 @@ struct Workspace {
   float* resid;
   uint16_t *normed, *q, *attn, *hidden;
   float *part_acc, *part_ml;
+  int2* attn_items;     // (sequence, unit) pairs that hold keys, built once per call
+  int32_t* attn_ctrl;   // [0] number of items, [1 + layer] work queue counter of that layer's attention launch
   float* split_part;   // fp32 partial of a split GEMM on the large-batch path, [m_pad][d_model]
   float2* amax;   // [m_pad][vocab/16] (value, index bits)
   size_t bytes;
@@ -125,6 +128,7 @@ void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hi
 void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const Workspace& ws, hipStream_t st);
 
 int attention_units(bool super_mode, int max_context);
+void launch_attention_plan(const llm42_model* m, int num_seqs, const Workspace& ws, hipStream_t st);
 void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv, int num_seqs, int window,
                       int max_context, const Workspace& ws, hipStream_t st);
 void launch_argmax_merge(const llm42_model* m, int num_seqs, int window, int32_t* out_tokens, const Workspace& ws,
