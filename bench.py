@@ -120,6 +120,7 @@ def main():
                     help="also run one plain elementwise kernel of known traffic (reads 256 MiB, writes 256 MiB) so "
                          "that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
     ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalid as a result)")
+    ap.add_argument("--no-check", action="store_true", help="debug only: do not compare the timed steps' outputs")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -191,7 +192,7 @@ def main():
         for _ in range(2):
             graph.replay()
         torch.cuda.synchronize()
-        assert torch.equal(out, eager_out), "graph replay differs from the eager step"
+        assert args.no_check or torch.equal(out, eager_out), "graph replay differs from the eager step"
     run = graph.replay if graph is not None else step
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -208,7 +209,7 @@ def main():
     torch.cuda.synchronize()
     dt_eager = time.perf_counter() - t2
     launches = B.llm42_profile_collect(args.steps * shape.n_layers)
-    assert torch.equal(out, eager_out)
+    assert args.no_check or torch.equal(out, eager_out)
     ms_per_step = dt * 1e3 / args.steps
     rows = num_seqs * window
     value = rows * args.steps / dt

@@ -105,7 +105,7 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   const size_t part_rows = (size_t)num_seqs * c.n_kv_heads * ws.attn_units * ws.r_pad;
   ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
   ws.part_ml = (float*)take(8ull * part_rows);
-  ws.attn_items = (int2*)take(sizeof(int2) * (size_t)num_seqs * ws.attn_units);
+  ws.attn_items = (int4*)take(sizeof(int4) * (size_t)num_seqs * ws.attn_units);
   ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (1 + c.n_layers));
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
   ws.split_part = (float*)take(ws.m_pad > 64 ? 4ull * ws.m_pad * c.d_model : 0);

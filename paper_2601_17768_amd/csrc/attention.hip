@@ -96,11 +96,127 @@ __device__ __forceinline__ float rows_sum(float x) {
   return __uint_as_float(r.x) + __uint_as_float(r.y);
 }
 
+// One online-softmax step over the 64 keys [k0, k0 + 64): `lk` / `lv` are the step's four K and
+// four V tiles in LDS.  MASKED = false is the same arithmetic with the comparisons that cannot
+// fail left out: every key of the step is at or below every position of this wave's rows (and
+// hence below k_hi).  The operand reads are issued one ring ahead of the MFMAs that consume them
+// and the order is pinned, so that an LDS round trip is never waited for in full.
+template <int HD, int CB, bool MASKED>
+__device__ __forceinline__ void softmax_step(const uint4* lk, const uint16_t* lv, int k0, int k_hi, int lane,
+                                             float scale_log2, const bf16x8 (&qf)[CB][HD / 32], const int (&qpos)[CB],
+                                             float (&m)[CB], float (&l)[CB], f32x4 (&acc)[CB][HD / 16]) {
+  constexpr int DK = HD / 32, DB = HD / 16, TV4 = HD * 2;
+  const int col = lane & 15, g = lane >> 4;
+  constexpr int RV = 4;                                     // V operands in flight
+  bf16x8 kb[DK];                                            // K operands in flight, one per head-dim k-step
+  u32x4 vb[RV];
+  auto load_k = [&](int b, int d) { kb[d] = ((const bf16x8*)lk)[b * TV4 + d * 64 + lane]; };
+  auto load_v = [&](int idx) {                              // idx = key pair kk * DB + feature block d
+    const uint16_t* vt0 = lv + (size_t)(2 * (idx / DB)) * TV4 * 8 + (((idx % DB) * 4 + g) * 16 + col) * 4;
+    const u32x2 lo = *(const u32x2*)vt0, hi = *(const u32x2*)(vt0 + TV4 * 8);
+    vb[idx % RV] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+  };
+  // ---- raw scores of 4 blocks of 16 keys: S^T[key][query] ---------------------------------
+  f32x4 sc[CB][4];
+#pragma unroll
+  for (int d = 0; d < DK; ++d) load_k(0, d);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+#pragma unroll
+    for (int d = 0; d < DK; ++d) {
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+        sc[cb][b] = mfma16(kb[d], qf[cb][d], d == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : sc[cb][b]);
+      if (b + 1 < 4) load_k(b + 1, d);
+      else if (d < RV) load_v(d);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int i = DK; i < RV; ++i) load_v(i);
+  // ---- mask, online softmax state (m in units of scaled scores), P in bf16 -----------------
+  u32x4 pf[CB][2];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    if (MASKED) {
+      // a select, not arithmetic: scores of keys past k_hi come from stale tiles and may be anything
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (k0 + b * 16 + g * 4 + e > qpos[cb]) sc[cb][b][e] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(sc[cb][0][0], sc[cb][0][1]), sc[cb][0][2]);
+    mx = fmaxf(fmaxf(mx, sc[cb][0][3]), sc[cb][1][0]);
+    mx = fmaxf(fmaxf(mx, sc[cb][1][1]), sc[cb][1][2]);
+    mx = fmaxf(fmaxf(mx, sc[cb][1][3]), sc[cb][2][0]);
+    mx = fmaxf(fmaxf(mx, sc[cb][2][1]), sc[cb][2][2]);
+    mx = fmaxf(fmaxf(mx, sc[cb][2][3]), sc[cb][3][0]);
+    mx = fmaxf(fmaxf(mx, sc[cb][3][1]), sc[cb][3][2]);
+    mx = rows_max(fmaxf(mx, sc[cb][3][3]));
+    // scaling by a positive constant is monotonic: max(scaled) == scaled(max), bit for bit
+    const float m_new = fmaxf(m[cb], mx * scale_log2);
+    const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m[cb] - m_use);
+    float rs = 0.f;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        sc[cb][b][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cb][b][e], scale_log2, -m_use));
+      rs += ((sc[cb][b][0] + sc[cb][b][1]) + sc[cb][b][2]) + sc[cb][b][3];
+    }
+    rs = rows_sum(rs);
+    l[cb] = l[cb] * alpha + rs;
+    m[cb] = m_new;
+#pragma unroll
+    for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
+    // k-slot e of lane group g is key g*4+e of the first block of a pair (e < 4) or of the
+    // second (e >= 4); V uses the same assignment
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      pf[cb][kk][0] = pack2_bf16(sc[cb][2 * kk][0], sc[cb][2 * kk][1]);
+      pf[cb][kk][1] = pack2_bf16(sc[cb][2 * kk][2], sc[cb][2 * kk][3]);
+      pf[cb][kk][2] = pack2_bf16(sc[cb][2 * kk + 1][0], sc[cb][2 * kk + 1][1]);
+      pf[cb][kk][3] = pack2_bf16(sc[cb][2 * kk + 1][2], sc[cb][2 * kk + 1][3]);
+    }
+  }
+  // ---- acc^T[feature][query] += V^T P^T, 32 keys per MFMA ------------------------------
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int idx = 0; idx < 2 * DB; ++idx) {
+    const int kk = idx / DB, d = idx % DB;
+    if (MASKED) {
+      // slots at or beyond k_hi hold stale, never-written or foreign data: force them to zero
+      // so that 0 * garbage cannot produce a NaN
+      const int kp0 = k0 + kk * 32 + g * 4, kp1 = kp0 + 16;
+      if (kp1 + 3 >= k_hi) {
+        u32x4& v = vb[idx % RV];
+        if (kp0 + 0 >= k_hi) v[0] &= 0xFFFF0000u;
+        if (kp0 + 1 >= k_hi) v[0] &= 0x0000FFFFu;
+        if (kp0 + 2 >= k_hi) v[1] &= 0xFFFF0000u;
+        if (kp0 + 3 >= k_hi) v[1] &= 0x0000FFFFu;
+        if (kp1 + 0 >= k_hi) v[2] &= 0xFFFF0000u;
+        if (kp1 + 1 >= k_hi) v[2] &= 0x0000FFFFu;
+        if (kp1 + 2 >= k_hi) v[3] &= 0xFFFF0000u;
+        if (kp1 + 3 >= k_hi) v[3] &= 0x0000FFFFu;
+      }
+    }
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+      acc[cb][d] = mfma16(__builtin_bit_cast(bf16x8, vb[idx % RV]), __builtin_bit_cast(bf16x8, pf[cb][kk]),
+                          acc[cb][d]);
+    if (idx + RV < 2 * DB) load_v(idx + RV);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int HD, int CB, int NW, bool SUPER>
 __global__ __launch_bounds__(NW * 64) void attention_kernel(
     const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
-    const int2* __restrict__ items, const int32_t* __restrict__ item_count, int32_t* __restrict__ queue,
+    const int4* __restrict__ items, const int32_t* __restrict__ item_count, int32_t* __restrict__ queue,
     int n_kv_heads, int group, int window, int r_pad, int y_blocks, int max_blocks_per_seq, int n_units,
     float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml) {
   constexpr int DK = HD / 32;        // MFMA k-steps over the head dimension (scores)
@@ -207,118 +323,6 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     }
   }
 
-  // One online-softmax step over the 64 keys [k0, k0 + 64): `lk` / `lv` are the step's four K and
-  // four V tiles in LDS.  MASKED = false is the same arithmetic with the comparisons that cannot
-  // fail left out: every key of the step is at or below every position of this wave's rows (and
-  // hence below k_hi).  With one wave per SIMD nothing hides an LDS round trip, so the operand
-  // reads are issued one group ahead of the MFMAs that consume them and the order is pinned.
-  auto step = [&](auto masked_c, const uint4* lk, const uint16_t* lv, int k0) {
-    constexpr bool MASKED = decltype(masked_c)::value;
-    constexpr int RV = 4;                                     // V operands in flight
-    bf16x8 kb[DK];                                            // K operands in flight, one per head-dim k-step
-    u32x4 vb[RV];
-    auto load_k = [&](int b, int d) { kb[d] = ((const bf16x8*)lk)[b * TV4 + d * 64 + lane]; };
-    auto load_v = [&](int idx) {                              // idx = key pair kk * DB + feature block d
-      const uint16_t* vt0 = lv + (size_t)(2 * (idx / DB)) * TV4 * 8 + (((idx % DB) * 4 + g) * 16 + col) * 4;
-      const u32x2 lo = *(const u32x2*)vt0, hi = *(const u32x2*)(vt0 + TV4 * 8);
-      vb[idx % RV] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-    };
-    // ---- raw scores of 4 blocks of 16 keys: S^T[key][query] ---------------------------------
-    f32x4 sc[CB][4];
-#pragma unroll
-    for (int d = 0; d < DK; ++d) load_k(0, d);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-#pragma unroll
-      for (int d = 0; d < DK; ++d) {
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-          sc[cb][b] = mfma16(kb[d], qf[cb][d], d == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : sc[cb][b]);
-        if (b + 1 < 4) load_k(b + 1, d);
-        else if (d < RV) load_v(d);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-#pragma unroll
-    for (int i = DK; i < RV; ++i) load_v(i);
-    // ---- mask, online softmax state (m in units of scaled scores), P in bf16 -----------------
-    u32x4 pf[CB][2];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-      if (MASKED) {
-        // a select, not arithmetic: scores of keys past k_hi come from stale tiles and may be anything
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (k0 + b * 16 + g * 4 + e > qpos[cb]) sc[cb][b][e] = -INFINITY;
-      }
-      float mx = fmaxf(fmaxf(sc[cb][0][0], sc[cb][0][1]), sc[cb][0][2]);
-      mx = fmaxf(fmaxf(mx, sc[cb][0][3]), sc[cb][1][0]);
-      mx = fmaxf(fmaxf(mx, sc[cb][1][1]), sc[cb][1][2]);
-      mx = fmaxf(fmaxf(mx, sc[cb][1][3]), sc[cb][2][0]);
-      mx = fmaxf(fmaxf(mx, sc[cb][2][1]), sc[cb][2][2]);
-      mx = fmaxf(fmaxf(mx, sc[cb][2][3]), sc[cb][3][0]);
-      mx = fmaxf(fmaxf(mx, sc[cb][3][1]), sc[cb][3][2]);
-      mx = rows_max(fmaxf(mx, sc[cb][3][3]));
-      // scaling by a positive constant is monotonic: max(scaled) == scaled(max), bit for bit
-      const float m_new = fmaxf(m[cb], mx * scale_log2);
-      const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m[cb] - m_use);
-      float rs = 0.f;
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          sc[cb][b][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cb][b][e], scale_log2, -m_use));
-        rs += ((sc[cb][b][0] + sc[cb][b][1]) + sc[cb][b][2]) + sc[cb][b][3];
-      }
-      rs = rows_sum(rs);
-      l[cb] = l[cb] * alpha + rs;
-      m[cb] = m_new;
-#pragma unroll
-      for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
-      // k-slot e of lane group g is key g*4+e of the first block of a pair (e < 4) or of the
-      // second (e >= 4); V uses the same assignment
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        pf[cb][kk][0] = pack2_bf16(sc[cb][2 * kk][0], sc[cb][2 * kk][1]);
-        pf[cb][kk][1] = pack2_bf16(sc[cb][2 * kk][2], sc[cb][2 * kk][3]);
-        pf[cb][kk][2] = pack2_bf16(sc[cb][2 * kk + 1][0], sc[cb][2 * kk + 1][1]);
-        pf[cb][kk][3] = pack2_bf16(sc[cb][2 * kk + 1][2], sc[cb][2 * kk + 1][3]);
-      }
-    }
-    // ---- acc^T[feature][query] += V^T P^T, 32 keys per MFMA ------------------------------
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int idx = 0; idx < 2 * DB; ++idx) {
-      const int kk = idx / DB, d = idx % DB;
-      if (MASKED) {
-        // slots at or beyond k_hi hold stale, never-written or foreign data: force them to zero
-        // so that 0 * garbage cannot produce a NaN
-        const int kp0 = k0 + kk * 32 + g * 4, kp1 = kp0 + 16;
-        if (kp1 + 3 >= k_hi) {
-          u32x4& v = vb[idx % RV];
-          if (kp0 + 0 >= k_hi) v[0] &= 0xFFFF0000u;
-          if (kp0 + 1 >= k_hi) v[0] &= 0x0000FFFFu;
-          if (kp0 + 2 >= k_hi) v[1] &= 0xFFFF0000u;
-          if (kp0 + 3 >= k_hi) v[1] &= 0x0000FFFFu;
-          if (kp1 + 0 >= k_hi) v[2] &= 0xFFFF0000u;
-          if (kp1 + 1 >= k_hi) v[2] &= 0x0000FFFFu;
-          if (kp1 + 2 >= k_hi) v[3] &= 0xFFFF0000u;
-          if (kp1 + 3 >= k_hi) v[3] &= 0x0000FFFFu;
-        }
-      }
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-        acc[cb][d] = mfma16(__builtin_bit_cast(bf16x8, vb[idx % RV]), __builtin_bit_cast(bf16x8, pf[cb][kk]),
-                            acc[cb][d]);
-      if (idx + RV < 2 * DB) load_v(idx + RV);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-
   // Steps j+1 .. j+AHEAD are in flight while step j is computed.  A buffer is refilled only after the
   // barrier that ends the step which read it; the wait before that barrier leaves the younger
   // fetches in flight (loads complete in order).
@@ -333,8 +337,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
       const int k0 = k_lo + j * STEP;
       const uint4* sk = &lds_k[j & (NBUF - 1)][0];
       const uint16_t* sv = (const uint16_t*)&lds_v[j & (NBUF - 1)][0];
-      if (k0 + STEP - 1 <= wmin) step(std::false_type{}, sk, sv, k0);    // wave-uniform
-      else step(std::true_type{}, sk, sv, k0);
+      if (k0 + STEP - 1 <= wmin)                               // wave-uniform
+        softmax_step<HD, CB, false>(sk, sv, k0, k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+      else
+        softmax_step<HD, CB, true>(sk, sv, k0, k_hi, lane, scale_log2, qf, qpos, m, l, acc);
     }
     if (SUPER && ((j & 3) == 3 || j + 1 == n_steps)) {
       // a chunk is complete: fold it into the running super partial and start the next one afresh
@@ -382,7 +388,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
   const int total = *item_count * per_item;
   for (int t = blockIdx.x; t < total;) {
     const int it = t / per_item, rem = t - it * per_item;
-    const int2 su = items[it];
+    const int4 su = items[it];
     run_item(su.y, rem % y_blocks, su.x, rem / y_blocks);
     __syncthreads();                                       // every wave is done with the ring
     if (threadIdx.x == 0) next_work = (int)gridDim.x + atomicAdd(queue, 1);
@@ -391,44 +397,208 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
   }
 }
 
-// The (sequence, unit) pairs that hold keys, full units first (long items first keeps the tail of
-// the launch short), and the per-layer queue counters.  One workgroup; runs once per call.
+// The same computation for 8 or more blocks of query rows per (sequence, kv head), as one stream per
+// CU.  A workgroup of 8 waves (one block of 16 query rows each) walks its share of the work items
+// (item t of round r goes to workgroup t mod G, rounds alternating direction, items sorted longest
+// first: an even split without a queue).  Everything it needs from global memory arrives through one
+// ring of LDS entries that never stops at an item boundary: per item first an entry with the eight
+// row blocks' query operands, then one entry (4 K tiles + 4 V tiles) per 64-key step, AHEAD entries
+// in flight.  A fetch cursor and a compute cursor walk the same item list independently; all item
+// data they need is wave-uniform and comes through scalar loads, so nothing but the ring's own
+// fetches is ever counted by vmcnt between the first and the last entry.  Past the last item the
+// fetch cursor issues dummy fetches into slots nothing reads, which keeps the wait count constant.
+template <int HD, bool SUPER>
+__global__ __launch_bounds__(512) void attention_stream_kernel(
+    const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
+    const int32_t* __restrict__ block_table, const int4* __restrict__ items, const int32_t* __restrict__ item_count,
+    int n_kv_heads, int group, int window, int r_pad, int y_blocks, int max_blocks_per_seq, int n_units,
+    float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml) {
+  constexpr int NW = 8, CB = 1;
+  constexpr int DK = HD / 32, DB = HD / 16, TV4 = HD * 2, TL = TV4 / 64;
+  constexpr int UNIT = SUPER ? SUPER_KEYS : CHUNK;
+  constexpr int NBUF = 4, AHEAD = 3;
+  constexpr int FI = TL;                // fetch instructions per wave per entry
+  static_assert(TL % 2 == 0, "half a tile per wave");
+  __shared__ uint4 ring[NBUF][8 * TV4];
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int col = lane & 15, g = lane >> 4;
+  const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_ptr)&ring[0][0];
+  const int G = gridDim.x, w = blockIdx.x;
+  const int per_item = n_kv_heads * y_blocks;
+  const int total = *item_count * per_item;
+
+  // the ord-th piece of work of this workgroup (wave-uniform; scalar loads)
+  struct Work {
+    bool valid;
+    int s, kvh, yb, unit, L, n, k_lo, k_hi, n_steps;
+  };
+  auto work_of = [&](int ord) {
+    Work x;
+    const int t = ord * G + ((ord & 1) ? G - 1 - w : w);
+    x.valid = t < total;
+    const int tt = x.valid ? t : 0;
+    const int it = tt / per_item, rem = tt - it * per_item;
+    // (past the end: a harmless stand-in, so that the dummy fetches read valid memory)
+    const int4 su = x.valid ? items[it] : make_int4(0, 0, 0, 1);
+    x.s = su.x, x.unit = su.y, x.L = su.z, x.n = su.w;
+    x.kvh = rem / y_blocks, x.yb = rem % y_blocks;
+    x.k_lo = x.unit * UNIT;
+    x.k_hi = min(x.L + x.n, x.k_lo + UNIT);
+    x.n_steps = (x.k_hi - x.k_lo + STEP - 1) / STEP;
+    return x;
+  };
+
+  // ---- fetch cursor ----------------------------------------------------------------------------
+  int f_ord = 0, f_entry = 0;           // entry 0 = query operands, entry e > 0 = step e - 1
+  Work f = work_of(0);
+  int f_id = 0;                         // block id this wave needs for the entry at the cursor (steps only)
+  const int blk = wave >> 1, part = wave & 1;
+  auto id_for = [&](const Work& x, int e) {   // physical block of this wave's 16 keys of step e - 1
+    const int b = min((x.k_lo >> 4) + (e - 1) * 4 + blk, (x.k_hi - 1) >> 4);   // never past the last block in use
+    return block_table[(size_t)x.s * max_blocks_per_seq + b];
+  };
+  auto fetch_next = [&](int gidx) {
+    const uint32_t slot = ring_addr + (uint32_t)((gidx & (NBUF - 1)) * 8 * TV4) * 16;
+    if (!f.valid || f_entry == 0) {
+      // this wave's block of 16 query rows (row blocks past r_pad read the last real one; past the
+      // last item: the same fetch once more, into a slot nothing reads)
+      const int rb = min(f.yb * NW + wave, r_pad / 16 - 1);
+      const uint4* src = (const uint4*)(q + ((size_t)f.s * n_kv_heads + f.kvh) * r_pad * HD + (size_t)rb * DK * 512);
+      tile_to_lds<TL>(slot + (uint32_t)(wave * TV4) * 16, src + lane);
+    } else {
+      const size_t src = ((size_t)f_id * n_kv_heads + f.kvh) * TV4 + part * (TL / 2) * 64 + lane;
+      const uint32_t off = (uint32_t)(blk * TV4 + part * (TL / 2) * 64) * 16;
+      tile_to_lds<TL / 2>(slot + off, k_plane + src);
+      tile_to_lds<TL / 2>(slot + (uint32_t)(4 * TV4) * 16 + off, v_plane + src);
+    }
+    if (f.valid) {
+      if (++f_entry > f.n_steps) {
+        f = work_of(++f_ord);
+        f_entry = 0;
+      } else {
+        f_id = id_for(f, f_entry);      // requested one entry ahead of its use
+      }
+    }
+  };
+
+  // ---- compute cursor ---------------------------------------------------------------------------
+#pragma unroll
+  for (int e = 0; e < AHEAD; ++e) fetch_next(e);
+  fetch_wait<(AHEAD - 1) * FI>();       // entry 0 has landed
+  __syncthreads();
+  int gidx = 0;                         // ring entry being consumed
+  auto entry_done = [&]() {
+    fetch_wait<(AHEAD - 1) * FI>();     // the next entry has landed: only the fetches issued after it may be outstanding
+    __syncthreads();                    // ... for every wave, and every wave is done with this entry's slot
+    ++gidx;
+  };
+  Work c = work_of(0);
+  for (int ord = 0; c.valid; ++ord) {
+    const Work c_next = work_of(ord + 1);   // requested now, needed when this item is done
+    // -- entry 0: query operands; per-lane row data
+    fetch_next(gidx + AHEAD);
+    bf16x8 qf[CB][DK];
+#pragma unroll
+    for (int d = 0; d < DK; ++d) qf[0][d] = ((const bf16x8*)ring[gidx & (NBUF - 1)])[wave * TV4 + d * 64 + lane];
+    int row[CB], qpos[CB];
+    row[0] = (c.yb * NW + wave) * 16 + col;
+    {
+      const int i = row[0] % window;
+      qpos[0] = (row[0] < group * window && i < c.n) ? c.L + i : -1;
+    }
+    int wmin = qpos[0];               // lowest position among this wave's rows (dead rows: -1)
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) wmin = min(wmin, __shfl_xor(wmin, off));
+    wmin = __builtin_amdgcn_readfirstlane(wmin);
+    float m[CB] = {-INFINITY}, l[CB] = {0.f}, sm[CB] = {-INFINITY}, sl[CB] = {0.f};
+    f32x4 acc[CB][DB], sacc[CB][DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      acc[0][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      sacc[0][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    entry_done();
+    // -- one entry per step
+    for (int j = 0; j < c.n_steps; ++j) {
+      fetch_next(gidx + AHEAD);
+      const int k0 = c.k_lo + j * STEP;
+      const uint4* sk = &ring[gidx & (NBUF - 1)][0];
+      const uint16_t* sv = (const uint16_t*)&ring[gidx & (NBUF - 1)][4 * TV4];
+      if (k0 + STEP - 1 <= wmin)                               // wave-uniform
+        softmax_step<HD, CB, false>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+      else
+        softmax_step<HD, CB, true>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+      if (SUPER && ((j & 3) == 3 || j + 1 == c.n_steps)) {
+        // a chunk is complete: fold it into the running super partial and start the next one afresh
+        if (j < 4) {
+          sm[0] = m[0];
+          sl[0] = l[0];
+#pragma unroll
+          for (int d = 0; d < DB; ++d) sacc[0][d] = acc[0][d];
+        } else {
+          fold<DB>(sm[0], sl[0], sacc[0], m[0], l[0], acc[0]);
+        }
+        m[0] = -INFINITY;
+        l[0] = 0.f;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) acc[0][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+      entry_done();
+    }
+    // -- partial of this unit for every row that reaches into it
+    if (qpos[0] >= c.k_lo) {
+      const size_t prow = (((size_t)c.s * n_kv_heads + c.kvh) * n_units + c.unit) * r_pad + row[0];
+      float* pa = part_acc + prow * HD;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) *(f32x4*)(pa + d * 16 + g * 4) = SUPER ? sacc[0][d] : acc[0][d];
+      if (g == 0) *(float2*)(part_ml + prow * 2) = SUPER ? make_float2(sm[0], sl[0]) : make_float2(m[0], l[0]);
+    }
+    c = c_next;
+  }
+  fetch_wait<0>();                      // the dummy fetches too
+}
+
+// The work items of a call: every (sequence, unit) pair that holds keys, as (s, unit, L, n), sorted
+// by the number of 64-key steps it takes, longest first (the attention kernels deal them out in that
+// order, which keeps the tail of a launch short); and the per-layer queue counters.  The order
+// inside a class of equal length is whatever the slot counter gives: it decides only which
+// workgroup computes an item, never a bit of the result.  One workgroup; runs once per call.
 __global__ __launch_bounds__(256) void attention_plan_kernel(const int32_t* __restrict__ seq_len,
                                                              const int32_t* __restrict__ seq_n, int num_seqs,
-                                                             int unit_keys, int2* __restrict__ items,
+                                                             int unit_keys, int4* __restrict__ items,
                                                              int32_t* __restrict__ item_count,
                                                              int32_t* __restrict__ queues, int n_layers) {
-  __shared__ int scan[256];
-  __shared__ int base;
-  if (threadIdx.x == 0) base = 0;
+  constexpr int MAXB = SUPER_KEYS / STEP;                  // classes: steps per item, 1 .. unit_keys / 64
+  __shared__ int count[MAXB + 1], cursor[MAXB + 1];
+  const int nb = unit_keys / STEP;
   for (int l = threadIdx.x; l < n_layers; l += 256) queues[l] = 0;
+  if (threadIdx.x <= MAXB) count[threadIdx.x] = 0;
   __syncthreads();
-  for (int pass = 0; pass < 2; ++pass) {                   // 0: units fully covered by keys, 1: the last, partial unit
-    for (int s0 = 0; s0 < num_seqs; s0 += 256) {
-      const int s = s0 + threadIdx.x;
-      int first = 0, cnt = 0;
-      if (s < num_seqs && seq_len[s] >= 0) {
-        const int keys = seq_len[s] + seq_n[s];              // positions 0 .. keys-1 are attended to
-        const int full = keys / unit_keys;
-        if (pass == 0) cnt = full;
-        else { first = full; cnt = keys % unit_keys ? 1 : 0; }
-      }
-      scan[threadIdx.x] = cnt;
-      __syncthreads();
-      for (int off = 1; off < 256; off <<= 1) {              // inclusive scan
-        const int v = threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
-        __syncthreads();
-        scan[threadIdx.x] += v;
-        __syncthreads();
-      }
-      const int at = base + scan[threadIdx.x] - cnt;
-      for (int u = 0; u < cnt; ++u) items[at + u] = make_int2(s, first + u);
-      __syncthreads();
-      if (threadIdx.x == 255) base += scan[255];
-      __syncthreads();
-    }
+  auto steps_of = [&](int keys, int u) { return (min(keys, (u + 1) * unit_keys) - u * unit_keys + STEP - 1) / STEP; };
+  for (int s = threadIdx.x; s < num_seqs; s += 256) {
+    if (seq_len[s] < 0) continue;
+    const int keys = seq_len[s] + seq_n[s];                // positions 0 .. keys-1 are attended to
+    const int full = keys / unit_keys;
+    if (full) atomicAdd(&count[nb], full);
+    if (keys % unit_keys) atomicAdd(&count[steps_of(keys, full)], 1);
   }
-  if (threadIdx.x == 0) *item_count = base;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int at = 0;
+    for (int c = nb; c >= 1; --c) {                        // longest class first
+      cursor[c] = at;
+      at += count[c];
+    }
+    *item_count = at;
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < num_seqs; s += 256) {
+    if (seq_len[s] < 0) continue;
+    const int L = seq_len[s], n = seq_n[s], keys = L + n;
+    const int units = (keys + unit_keys - 1) / unit_keys;
+    for (int u = 0; u < units; ++u) items[atomicAdd(&cursor[steps_of(keys, u)], 1)] = make_int4(s, u, L, n);
+  }
 }
 
 // Fold the partials of every query row (chunks inside a super left to right, then the supers
@@ -517,17 +687,34 @@ void launch_one(const llm42_model* m, int layer, const uint16_t* kp, const uint1
                                                window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
 }
 
+template <int HD, bool SUPER>
+void launch_stream(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
+                   int window, const Workspace& ws, hipStream_t st) {
+  const llm42_config& c = m->cfg;
+  const float scale_log2 = (1.0f / sqrtf((float)c.head_dim)) * 1.44269504088896340736f;
+  const int y_blocks = (ws.r_pad / 16 + 7) / 8;
+  const long long max_items = (long long)num_seqs * ws.attn_units * c.n_kv_heads * y_blocks;
+  const unsigned grid = (unsigned)std::min<long long>(m->num_cus * (HD == 128 ? 1 : 2), max_items);
+  attention_stream_kernel<HD, SUPER><<<grid, 512, 0, st>>>(
+      ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table, ws.attn_items, ws.attn_ctrl, c.n_kv_heads, m->group,
+      window, ws.r_pad, y_blocks, kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc, ws.part_ml);
+  const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
+  attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
+                                      0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
+                                               window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
+}
+
 template <int HD>
 void launch_hd(const llm42_model* m, int layer, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv,
                int num_seqs, int window, const Workspace& ws, hipStream_t st) {
   // 8 row blocks or more per (sequence, kv head): 8 waves of one row block each, two per SIMD, so
-  // that one wave's MFMAs run under the other's softmax arithmetic; fewer: 4 waves.
+  // that one wave's MFMAs run under the other's softmax arithmetic, as one stream per CU; fewer: 4 waves.
   const bool wide = ws.r_pad / 16 >= 8;
   if (ws.attn_super) {
-    if (wide) launch_one<HD, 1, 8, true>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_stream<HD, true>(m, kp, vp, kv, num_seqs, window, ws, st);
     else launch_one<HD, 1, 4, true>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   } else {
-    if (wide) launch_one<HD, 1, 8, false>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_stream<HD, false>(m, kp, vp, kv, num_seqs, window, ws, st);
     else launch_one<HD, 1, 4, false>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   }
 }

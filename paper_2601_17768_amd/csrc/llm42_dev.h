@@ -96,7 +96,7 @@ struct Workspace {
   float* resid;
   uint16_t *normed, *q, *attn, *hidden;
   float *part_acc, *part_ml;
-  int2* attn_items;     // (sequence, unit) pairs that hold keys, built once per call
+  int4* attn_items;     // (sequence, unit, length, rows) of every unit that holds keys, built once per call
   int32_t* attn_ctrl;   // [0] number of items, [1 + layer] work queue counter of that layer's attention launch
   float* split_part;   // fp32 partial of a split GEMM on the large-batch path, [m_pad][d_model]
   float2* amax;   // [m_pad][vocab/16] (value, index bits)
