@@ -193,7 +193,17 @@ enum {
   LLM42_K_GATE_UP, LLM42_K_DOWN, LLM42_K_LM_HEAD, LLM42_K_ARGMAX, LLM42_K_COMMIT, LLM42_K_COUNT
 };
 llm42_status llm42_profile_enable(int32_t kind, int32_t max_launches);
+
 llm42_status llm42_profile_collect(float* ms_out, int32_t* kinds_out, int32_t capacity, int32_t* n_out);
+
+/* Measurement aid for the cost of determinism (not part of the protocol; process-wide, not thread
+ * safe).  With on != 0 the next calls drop the two places where the fixed reduction schedule costs
+ * time and let the batch decide instead, as an ordinary engine would: with more than 64 rows the two
+ * residual projections are not split along k (one accumulator per element instead of p0 + p1), and
+ * an attention workgroup that owns a whole 2048-key super accumulates straight through it instead of
+ * closing a partial every 256 keys.  Results then stay within rounding of the scheduled ones but are
+ * no longer bitwise independent of the batch.  bench.py times one pass each way; nothing else sets it. */
+void llm42_measure_unconstrained(int32_t on);
 
 /* Description of the last error on this thread (host string, never NULL). */
 const char* llm42_last_error(void);

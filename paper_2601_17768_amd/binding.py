@@ -24,7 +24,7 @@ LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
            "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
-           "llm42_profile_enable", "llm42_profile_collect")
+           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
                   "argmax", "commit")
 
@@ -84,6 +84,8 @@ def load_library(path: Optional[str] = None):
     lib.llm42_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32,
                                           ctypes.POINTER(i32)]
     lib.llm42_profile_collect.restype = i32
+    lib.llm42_measure_unconstrained.argtypes = [i32]
+    lib.llm42_measure_unconstrained.restype = None
     lib.llm42_last_error.argtypes = []
     lib.llm42_last_error.restype = ctypes.c_char_p
     lib.llm42_schedule_info.argtypes = []
@@ -189,6 +191,11 @@ def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_
 
 def llm42_schedule_info() -> str:
     return load_library().llm42_schedule_info().decode()
+
+
+def llm42_measure_unconstrained(on: bool) -> None:
+    """Measurement only: lift (or restore) the fixed reduction schedule, see llm42.h."""
+    load_library().llm42_measure_unconstrained(1 if on else 0)
 
 
 def llm42_profile_enable(kind, max_launches: int) -> None:

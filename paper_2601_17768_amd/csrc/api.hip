@@ -115,9 +115,13 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
 
 }  // namespace
 
+int g_llm42_unconstrained = 0;
+
 extern "C" {
 
 const char* llm42_last_error(void) { return g_err; }
+
+void llm42_measure_unconstrained(int32_t on) { g_llm42_unconstrained = on ? 1 : 0; }
 
 const char* llm42_schedule_info(void) {
   return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=2 (halves, p0+p1) for the two residual projections, 1 elsewhere; "

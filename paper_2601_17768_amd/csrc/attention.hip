@@ -407,7 +407,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
 // data they need is wave-uniform and comes through scalar loads, so nothing but the ring's own
 // fetches is ever counted by vmcnt between the first and the last entry.  Past the last item the
 // fetch cursor issues dummy fetches into slots nothing reads, which keeps the wait count constant.
-template <int HD, bool SUPER>
+// FOLD = false (measurement only): no chunk partials inside a super, one straight accumulation.
+template <int HD, bool SUPER, bool FOLD>
 __global__ __launch_bounds__(512) void attention_stream_kernel(
     const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int4* __restrict__ items, const int32_t* __restrict__ item_count,
@@ -529,7 +530,7 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
         softmax_step<HD, CB, false>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
       else
         softmax_step<HD, CB, true>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
-      if (SUPER && ((j & 3) == 3 || j + 1 == c.n_steps)) {
+      if (SUPER && FOLD && ((j & 3) == 3 || j + 1 == c.n_steps)) {
         // a chunk is complete: fold it into the running super partial and start the next one afresh
         if (j < 4) {
           sm[0] = m[0];
@@ -551,8 +552,9 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
       const size_t prow = (((size_t)c.s * n_kv_heads + c.kvh) * n_units + c.unit) * r_pad + row[0];
       float* pa = part_acc + prow * HD;
 #pragma unroll
-      for (int d = 0; d < DB; ++d) *(f32x4*)(pa + d * 16 + g * 4) = SUPER ? sacc[0][d] : acc[0][d];
-      if (g == 0) *(float2*)(part_ml + prow * 2) = SUPER ? make_float2(sm[0], sl[0]) : make_float2(m[0], l[0]);
+      for (int d = 0; d < DB; ++d) *(f32x4*)(pa + d * 16 + g * 4) = SUPER && FOLD ? sacc[0][d] : acc[0][d];
+      if (g == 0)
+        *(float2*)(part_ml + prow * 2) = SUPER && FOLD ? make_float2(sm[0], sl[0]) : make_float2(m[0], l[0]);
     }
     c = c_next;
   }
@@ -687,7 +689,7 @@ void launch_one(const llm42_model* m, int layer, const uint16_t* kp, const uint1
                                                window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
 }
 
-template <int HD, bool SUPER>
+template <int HD, bool SUPER, bool FOLD>
 void launch_stream(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
                    int window, const Workspace& ws, hipStream_t st) {
   const llm42_config& c = m->cfg;
@@ -695,7 +697,7 @@ void launch_stream(const llm42_model* m, const uint16_t* kp, const uint16_t* vp,
   const int y_blocks = (ws.r_pad / 16 + 7) / 8;
   const long long max_items = (long long)num_seqs * ws.attn_units * c.n_kv_heads * y_blocks;
   const unsigned grid = (unsigned)std::min<long long>(m->num_cus * (HD == 128 ? 1 : 2), max_items);
-  attention_stream_kernel<HD, SUPER><<<grid, 512, 0, st>>>(
+  attention_stream_kernel<HD, SUPER, FOLD><<<grid, 512, 0, st>>>(
       ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table, ws.attn_items, ws.attn_ctrl, c.n_kv_heads, m->group,
       window, ws.r_pad, y_blocks, kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc, ws.part_ml);
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
@@ -711,10 +713,11 @@ void launch_hd(const llm42_model* m, int layer, const uint16_t* kp, const uint16
   // that one wave's MFMAs run under the other's softmax arithmetic, as one stream per CU; fewer: 4 waves.
   const bool wide = ws.r_pad / 16 >= 8;
   if (ws.attn_super) {
-    if (wide) launch_stream<HD, true>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide && g_llm42_unconstrained) launch_stream<HD, true, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    else if (wide) launch_stream<HD, true, true>(m, kp, vp, kv, num_seqs, window, ws, st);
     else launch_one<HD, 1, 4, true>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   } else {
-    if (wide) launch_stream<HD, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide) launch_stream<HD, false, true>(m, kp, vp, kv, num_seqs, window, ws, st);
     else launch_one<HD, 1, 4, false>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   }
 }

@@ -127,6 +127,9 @@ void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, in
 void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hipStream_t st);
 void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const Workspace& ws, hipStream_t st);
 
+// Measurement only (llm42_measure_unconstrained): the reduction schedule may then follow the batch.
+extern int g_llm42_unconstrained;
+
 int attention_units(bool super_mode, int max_context);
 void launch_attention_plan(const llm42_model* m, int num_seqs, const Workspace& ws, hipStream_t st);
 void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv, int num_seqs, int window,

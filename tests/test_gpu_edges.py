@@ -78,3 +78,33 @@ def test_window_of_one_row(tiny):
 
 def test_contexts_around_step_and_chunk_boundaries(tiny):
     _run_and_compare(tiny, lens=[56, 63, 64, 248, 255, 256, 257, 511, 512], window=8, n_valid=None, seed=103)
+
+
+def test_lifting_the_schedule_changes_rounding_only(tiny):
+    """llm42_measure_unconstrained (bench only) lets the batch choose the split of the residual
+    projections: the logits move by rounding, nothing else, and the switch goes back cleanly."""
+    from paper_2601_17768_amd import binding as B
+    shape, w, sess = tiny
+    rng = wl.rng_for(104, 1)
+    lens = np.array([40, 90, 130], dtype=np.int32)
+    window = 64                                  # 192 rows: above the 64-row limit of the small-batch kernels
+    table, num_blocks = wl.make_block_table(rng, lens + window, 16, spare_blocks=2)
+    kv = sess.kv_cache(num_blocks)
+    kv.normal_(generator=torch.Generator(device=DEV).manual_seed(5))
+    bt = torch.as_tensor(table, device=DEV)
+    cand = torch.as_tensor(wl.random_tokens(rng, 3 * window, shape.vocab).reshape(3, window).astype(np.int32), device=DEV)
+    dump = torch.arange(3, dtype=torch.int32, device=DEV)
+    sl = torch.as_tensor(lens, device=DEV)
+    _, _, fixed = sess.verify(kv, bt, sl, cand, dump_seq_ids=dump)
+    fixed = fixed.clone()
+    B.llm42_measure_unconstrained(True)
+    try:
+        _, _, free = sess.verify(kv, bt, sl, cand, dump_seq_ids=dump)
+        free = free.clone()
+    finally:
+        B.llm42_measure_unconstrained(False)
+    _, _, again = sess.verify(kv, bt, sl, cand, dump_seq_ids=dump)
+    torch.cuda.synchronize()
+    assert torch.equal(again, fixed)
+    assert not torch.equal(free, fixed)          # a different reduction order does show in the last bits
+    assert float((free - fixed).abs().max()) < 2e-2   # the logit tolerance; measured 4e-3 (bf16 rounding points amplify last-bit differences)
