@@ -78,6 +78,7 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   const llm42_config& c = m->cfg;
   Workspace ws;
   memset(&ws, 0, sizeof ws);
+  ws.num_cus = m->num_cus;
   ws.m_rows = num_seqs * window;
   ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : ws.m_rows <= 64 ? 64
              : ws.m_rows <= 512 ? pad_to(ws.m_rows, 128) : pad_to(ws.m_rows, 256);

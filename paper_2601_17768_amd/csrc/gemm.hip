@@ -564,8 +564,12 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
     return;
   }
   // more than 64 tokens: m_pad is a multiple of 128 (up to 512 rows) or of 256 (beyond)
-  if (m_pad >= 512 && m_pad % 256 == 0) launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
-  else launch_tiled<4, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  // 128 x 256 tiles when they fill the device (two workgroups per CU) at least once, else 128 x 128
+  const long long big_tiles = (long long)((n_blocks + 7) / 8) * (m_pad / 256);
+  if (m_pad >= 512 && m_pad % 256 == 0 && big_tiles >= 2LL * ws.num_cus)
+    launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  else
+    launch_tiled<4, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
 }
 
 }  // namespace

@@ -87,6 +87,7 @@ struct llm42_model {
 
 // Workspace carving, identical in llm42_workspace_bytes and llm42_verify_window.
 struct Workspace {
+  int num_cus;    // compute units of the device
   int m_rows;     // num_seqs * window
   int m_pad;      // rows padded for the GEMM grid
   int r_pad;      // query rows per (seq, kv head) padded to 16
