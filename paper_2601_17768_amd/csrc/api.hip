@@ -98,6 +98,8 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.seq_len = (int32_t*)take(sizeof(int32_t) * num_seqs);
   ws.seq_n = (int32_t*)take(sizeof(int32_t) * num_seqs);
   ws.dump_slot = (int32_t*)take(sizeof(int32_t) * num_seqs);
+  ws.row_blk = (int32_t*)take(sizeof(int32_t) * ws.m_pad);
+  ws.row_rope = (float2*)take(sizeof(float2) * (size_t)ws.m_pad * (c.head_dim / 2));
   ws.resid = (float*)take(4ull * ws.m_pad * c.d_model);
   ws.normed = (uint16_t*)take(2ull * ws.m_pad * c.d_model);
   ws.q = (uint16_t*)take(2ull * num_seqs * c.n_kv_heads * ws.r_pad * c.head_dim);

@@ -15,17 +15,19 @@
 namespace {
 
 struct QkvEpi {
-  const float2* __restrict__ rope;        // [max_position][head_dim/2] (cos, sin)
+  const float4* __restrict__ row_rope;    // [row][head_dim/4]: (cos, sin) of two consecutive rotary pairs at the row's position
   const int32_t* __restrict__ row_pos;
   const int32_t* __restrict__ row_seq;
-  const int32_t* __restrict__ block_table;
+  const int32_t* __restrict__ row_blk;    // physical KV block of the row's position
   uint16_t* q;               // [seq][kv head][r_pad][head_dim] tile layout, r = q-head-in-group * window + i
   uint16_t* k_plane;         // this layer's K tiles [block][kv head][16*head_dim]
   uint16_t* v_plane;
-  int n_q_heads, n_kv_heads, head_dim, group, window, r_pad, max_blocks_per_seq;
+  int n_q_heads, n_kv_heads, head_dim, group, window, r_pad;
 
   // What the epilogue needs from memory besides the accumulators; requested when the kernel
-  // starts so that its latency hides behind the weight stream.
+  // starts so that its latency hides behind the weight stream.  Everything is indexed by the row
+  // alone (the per-row block id and rotary factors are laid out once per call), so none of these
+  // loads waits for another.
   struct Row {   // per token row
     int pos, s, blk;
   };
@@ -37,7 +39,7 @@ struct QkvEpi {
     Row r;
     r.pos = row_pos[row];
     r.s = row_seq[row];
-    r.blk = block_table[(size_t)r.s * max_blocks_per_seq + (max(r.pos, 0) >> 4)];
+    r.blk = row_blk[row];
     return r;
   }
   __device__ Pre pre(int nb, int lane, int row, const Row& r) const {
@@ -45,10 +47,10 @@ struct QkvEpi {
     p.pos = r.pos;
     p.s = r.s;
     p.blk = r.blk;
-    const int safe = max(r.pos, 0);
     const int j0 = (nb % (head_dim >> 4)) * 8 + (lane >> 4) * 2;
-    p.cs0 = rope[(size_t)safe * (head_dim >> 1) + j0];
-    p.cs1 = rope[(size_t)safe * (head_dim >> 1) + j0 + 1];
+    const float4 cs = row_rope[(size_t)row * (head_dim >> 2) + (j0 >> 1)];
+    p.cs0 = make_float2(cs.x, cs.y);
+    p.cs1 = make_float2(cs.z, cs.w);
     return p;
   }
   __device__ void operator()(int nb, int lane, int row, const f32x4 acc, const Pre& p) const {
@@ -579,10 +581,10 @@ void launch_gemm_qkv(const llm42_model* m, int layer, const llm42_kv_cache* kv, 
   const llm42_config& c = m->cfg;
   const size_t plane = (size_t)kv->num_blocks * c.n_kv_heads * 16 * c.head_dim;
   QkvEpi e;
-  e.rope = (const float2*)m->rope;
+  e.row_rope = (const float4*)ws.row_rope;
   e.row_pos = ws.row_pos;
   e.row_seq = ws.row_seq;
-  e.block_table = kv->block_table;
+  e.row_blk = ws.row_blk;
   e.q = ws.q;
   e.k_plane = (uint16_t*)kv->kv_base + ((size_t)layer * 2 + 0) * plane;
   e.v_plane = (uint16_t*)kv->kv_base + ((size_t)layer * 2 + 1) * plane;
@@ -592,7 +594,6 @@ void launch_gemm_qkv(const llm42_model* m, int layer, const llm42_kv_cache* kv, 
   e.group = m->group;
   e.window = window;
   e.r_pad = ws.r_pad;
-  e.max_blocks_per_seq = kv->max_blocks_per_seq;
   launch_gemm<kSplit[GEMM_QKV]>(m->layers[layer].wqkv, ws.normed, m->n_qkv / 16, c.d_model, m->n_qkv, ws, false, e, st);
 }
 

@@ -94,6 +94,8 @@ struct Workspace {
   int attn_units; // attention partial slots per row (chunks or supers, see attention.hip)
   bool attn_super; // one workgroup per super (many sequences) instead of per chunk
   int32_t *row_pos, *row_seq, *seq_len, *seq_n, *dump_slot;
+  int32_t* row_blk;    // physical KV block that holds the row's position (0 for dead rows)
+  float2* row_rope;    // [m_pad][head_dim/2] (cos, sin) at the row's position
   float* resid;
   uint16_t *normed, *q, *attn, *hidden;
   float *part_acc, *part_ml;

@@ -13,7 +13,8 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
                                int max_blocks_per_seq, int64_t num_blocks, int window, int max_context, int vocab,
                                const int32_t* __restrict__ dump_seq_ids, int n_dump, int32_t* out_tokens,
                                int32_t* seq_status, int32_t* row_pos, int32_t* row_seq, int32_t* ws_len,
-                               int32_t* ws_n, int32_t* dump_slot) {
+                               int32_t* ws_n, int32_t* dump_slot, const float2* __restrict__ rope, int half_dim,
+                               int32_t* row_blk, float2* row_rope) {
   __shared__ int status;
   const int s = blockIdx.x;
   if (threadIdx.x == 0) status = 0;
@@ -41,7 +42,17 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
     const bool live = st == 0 && i < n;
     row_pos[row] = live ? L + i : -1;
     row_seq[row] = s;
+    // where the row's K and V go (a block id that passed the check above), for the QKV epilogue
+    row_blk[row] = live ? block_table[(size_t)s * max_blocks_per_seq + ((L + i) >> 4)] : 0;
     out_tokens[row] = -1;              // overwritten by the arg-max merge for live rows
+  }
+  // the rotary factors of every live row, laid out by row so that the QKV epilogue finds them without
+  // knowing the position first
+  if (st == 0) {
+    for (int e = threadIdx.x; e < n * half_dim; e += blockDim.x) {
+      const int i = e / half_dim, j = e - i * half_dim;
+      row_rope[(size_t)(s * window + i) * half_dim + j] = rope[(size_t)(L + i) * half_dim + j];
+    }
   }
   if (threadIdx.x == 0) {
     ws_len[s] = st == 0 ? L : -1;
@@ -55,11 +66,12 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
 }
 
 // Rows beyond num_seqs*window that only pad the GEMM grid.
-__global__ void prepare_pad_rows_kernel(int32_t* row_pos, int32_t* row_seq, int from, int to) {
+__global__ void prepare_pad_rows_kernel(int32_t* row_pos, int32_t* row_seq, int32_t* row_blk, int from, int to) {
   const int r = from + blockIdx.x * blockDim.x + threadIdx.x;
   if (r < to) {
     row_pos[r] = -1;
     row_seq[r] = 0;
+    row_blk[r] = 0;
   }
 }
 
@@ -205,10 +217,11 @@ void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_
   prepare_kernel<<<num_seqs, 64, 0, st>>>(seq_lens, candidates, n_valid, kv->block_table, kv->max_blocks_per_seq,
                                           kv->num_blocks, window, max_context, m->cfg.vocab, dump_seq_ids, n_dump,
                                           out_tokens, seq_status, ws.row_pos, ws.row_seq, ws.seq_len, ws.seq_n,
-                                          ws.dump_slot);
+                                          ws.dump_slot, (const float2*)m->rope, m->cfg.head_dim / 2, ws.row_blk,
+                                          ws.row_rope);
   if (ws.m_pad > ws.m_rows)
-    prepare_pad_rows_kernel<<<(ws.m_pad - ws.m_rows + 63) / 64, 64, 0, st>>>(ws.row_pos, ws.row_seq, ws.m_rows,
-                                                                            ws.m_pad);
+    prepare_pad_rows_kernel<<<(ws.m_pad - ws.m_rows + 63) / 64, 64, 0, st>>>(ws.row_pos, ws.row_seq, ws.row_blk,
+                                                                            ws.m_rows, ws.m_pad);
 }
 
 void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspace& ws, hipStream_t st) {
