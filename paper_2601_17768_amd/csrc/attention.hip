@@ -39,15 +39,25 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-// state <- state (+) part, the only way two partials are ever combined.
+// state <- state (+) part, the only way two partials are ever combined:
+//   mn = max(M, m2), a = exp2(M - mn), b = exp2(m2 - mn), L = fma(l2, b, L * a), A = fma(a2, b, A * a).
+// One of a, b is exactly 1; where a is 1 for every lane of the wave (the running maximum stands,
+// the usual case) the multiplication by it is left out, which cannot change a bit.
 template <int NV>
 __device__ inline void fold(float& M, float& L, f32x4 (&A)[NV], float m2, float l2, const f32x4 (&a2)[NV]) {
   const float mn = fmaxf(M, m2);
   const float mu = mn == -INFINITY ? 0.f : mn;
   const float a = __builtin_amdgcn_exp2f(M - mu), b = __builtin_amdgcn_exp2f(m2 - mu);
-  L = L * a + l2 * b;
+  if (__builtin_amdgcn_ballot_w64(a != 1.0f) != 0) {
+    L *= a;
 #pragma unroll
-  for (int i = 0; i < NV; ++i) A[i] = A[i] * a + a2[i] * b;
+    for (int i = 0; i < NV; ++i) A[i] *= a;
+  }
+  L = __builtin_fmaf(l2, b, L);
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) A[i][c] = __builtin_fmaf(a2[i][c], b, A[i][c]);
   M = mn;
 }
 

@@ -208,6 +208,56 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   }
 }
 
+// RMSNorm for many rows at d = 4096: one workgroup of 1024 threads per block of 16 rows, thread
+// (w, g, r) owning the partial sum p[w][g] of row r - the same 64 partials per row, accumulated in
+// the same order and combined in the same tree as in rmsnorm_kernel, so the bits are the same; only
+// the work distribution differs.  With 16 rows of a token block side by side every 16-byte piece of
+// the residual stream and of the output tiles is read or written as part of a full 256-byte run
+// (the wave-per-row kernel touches every 128-byte line for half of its bytes).
+__global__ __launch_bounds__(1024) void rmsnorm_block_kernel(const float* __restrict__ x,
+                                                             const uint16_t* __restrict__ gain,
+                                                             uint16_t* __restrict__ y, float eps) {
+  constexpr int D = 4096, U = 8;                         // tiles of 32 features per thread: t = u * 16 + w
+  __shared__ float part[64][16];
+  __shared__ float inv_s[16];
+  const int r = threadIdx.x & 15, wg = threadIdx.x >> 4, w = wg >> 2, g = wg & 3;
+  const int row = blockIdx.x * 16 + r;
+  const float* xr = x + resid_off(row, 0, D);
+  uint4* yr = (uint4*)(y + pk_off(row, 0, D));
+  f32x4 a[U], b[U];
+  uint4 gv[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int f = (u * 16 + w) * 32 + g * 8;
+    a[u] = *(const f32x4*)(xr + (f >> 2) * 64);
+    b[u] = *(const f32x4*)(xr + (f >> 2) * 64 + 64);
+    gv[u] = *(const uint4*)(gain + f);
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(a[u][i], a[u][i], ss);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(b[u][i], b[u][i], ss);
+  }
+  part[wg][r] = ss;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    float total = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 16; ++ww) {
+      const float s4 = (part[ww * 4][r] + part[ww * 4 + 1][r]) + (part[ww * 4 + 2][r] + part[ww * 4 + 3][r]);
+      total = ww == 0 ? s4 : total + s4;
+    }
+    inv_s[r] = 1.0f / __builtin_sqrtf(total / (float)D + eps);
+  }
+  __syncthreads();
+  const float inv = inv_s[r];
+#pragma unroll
+  for (int u = 0; u < U; ++u) emit_normed(yr, (u * 16 + w) * 32 + g * 8, a[u], b[u], gv[u], inv);
+}
+
 }  // namespace
 
 void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
@@ -231,5 +281,6 @@ void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspa
 
 void launch_rmsnorm(const float* x, const uint16_t* gain, uint16_t* y, int m_pad, int d, float eps,
                     hipStream_t st) {
-  rmsnorm_kernel<<<(m_pad + 3) / 4, 256, 0, st>>>(x, gain, y, m_pad, d, eps);
+  if (d == 4096 && m_pad >= 256 && m_pad % 16 == 0) rmsnorm_block_kernel<<<m_pad / 16, 1024, 0, st>>>(x, gain, y, eps);
+  else rmsnorm_kernel<<<(m_pad + 3) / 4, 256, 0, st>>>(x, gain, y, m_pad, d, eps);
 }
