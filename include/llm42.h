@@ -180,6 +180,20 @@ llm42_status llm42_commit_rollback(
     int32_t*       rolled_back_counts,  /* dev [num_seqs] or NULL, out       */
     void*          hip_stream);
 
+/* Fast path (SS 4.1: candidate tokens come from ordinary, high-throughput decoding whose reduction
+ * order follows the batch): one greedy decoding step for num_seqs sequences.  tokens[s] is the input
+ * token of sequence s at position seq_lens[s]; its K and V are written to that slot of the cache
+ * (an unverified entry: the next llm42_verify_window over the position overwrites it) and
+ * out_tokens[s] receives the arg-max token.  Same kernels as the verifier, but the split of the
+ * residual projections follows the number of rows (two k-halves up to 16 rows, none beyond), so the
+ * low bits of the logits - and now and then a token - depend on how many sequences are decoded
+ * together.  That is what the verifier exists to repair.  dev [num_seqs] arrays; workspace as for
+ * llm42_verify_window with window 1; errors and seq_status as there. */
+llm42_status llm42_decode_step(
+    const llm42_model* model, const llm42_kv_cache* kv_cache, const int32_t* seq_lens, const int32_t* tokens,
+    int32_t num_seqs, int32_t max_context, int32_t* out_tokens, int32_t* seq_status,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid (not part of the protocol; process-wide state, not thread safe).
  * While enabled, every kernel launch of class `kind` (LLM42_K_*, or -1 for all
  * classes) made by the two hot calls is bracketed by HIP events recorded on the
@@ -198,7 +212,7 @@ llm42_status llm42_profile_collect(float* ms_out, int32_t* kinds_out, int32_t ca
 
 /* Measurement aid for the cost of determinism (not part of the protocol; process-wide, not thread
  * safe).  With on != 0 the next calls drop the two places where the fixed reduction schedule costs
- * time and let the batch decide instead, as an ordinary engine would: with more than 64 rows the two
+ * time and let the batch decide instead, as an ordinary engine would: with more than 16 rows the two
  * residual projections are not split along k (one accumulator per element instead of p0 + p1), and
  * an attention workgroup that owns a whole 2048-key super accumulates straight through it instead of
  * closing a partial every 256 keys.  Results then stay within rounding of the scheduled ones but are

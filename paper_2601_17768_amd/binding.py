@@ -24,7 +24,7 @@ LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
            "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
-           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained")
+           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained", "llm42_decode_step")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
                   "argmax", "commit")
 
@@ -77,6 +77,8 @@ def load_library(path: Optional[str] = None):
     lib.llm42_verify_window.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, i32,
                                         vp, ctypes.c_size_t, vp]
     lib.llm42_verify_window.restype = i32
+    lib.llm42_decode_step.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.llm42_decode_step.restype = i32
     lib.llm42_commit_rollback.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.llm42_commit_rollback.restype = i32
     lib.llm42_profile_enable.argtypes = [i32, i32]
@@ -177,6 +179,19 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
         _ptr(n_valid, torch.int32), num_seqs, max_context, _ptr(out_tokens, torch.int32),
         _ptr(seq_status, torch.int32), _ptr(out_logits, torch.float32), _ptr(dump_seq_ids, torch.int32), n_dump,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def llm42_decode_step(model: int, kv_base: torch.Tensor, num_blocks: int, block_table: torch.Tensor,
+                      seq_lens: torch.Tensor, tokens: torch.Tensor, max_context: int, out_tokens: torch.Tensor,
+                      workspace: torch.Tensor, seq_status: Optional[torch.Tensor] = None, stream=None) -> None:
+    num_seqs = seq_lens.numel()
+    if tokens.numel() != num_seqs or out_tokens.numel() != num_seqs:
+        raise ValueError("tokens / out_tokens must hold one entry per sequence")
+    kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
+    _check(load_library().llm42_decode_step(
+        model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(tokens, torch.int32), num_seqs, max_context,
+        _ptr(out_tokens, torch.int32), _ptr(seq_status, torch.int32), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 
 def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_valid: Optional[torch.Tensor],

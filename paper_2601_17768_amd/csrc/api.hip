@@ -305,6 +305,17 @@ llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv,
   return LLM42_OK;
 }
 
+llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                               const int32_t* tokens, int32_t num_seqs, int32_t max_context, int32_t* out_tokens,
+                               int32_t* seq_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int saved = g_llm42_unconstrained;
+  g_llm42_unconstrained = 1;
+  const llm42_status st = llm42_verify_window(m, kv, seq_lens, tokens, 1, nullptr, num_seqs, max_context, out_tokens,
+                                              seq_status, nullptr, nullptr, 0, workspace, workspace_bytes, hip_stream);
+  g_llm42_unconstrained = saved;
+  return st;
+}
+
 llm42_status llm42_commit_rollback(const int32_t* candidates, const int32_t* out_tokens, const int32_t* n_valid,
                                    int32_t num_seqs, int32_t window, int32_t* seq_lens, int32_t* committed_counts,
                                    int32_t* committed_tokens, int32_t* rolled_back_counts, void* hip_stream) {

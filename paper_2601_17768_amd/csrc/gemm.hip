@@ -600,7 +600,9 @@ void launch_gemm_qkv(const llm42_model* m, int layer, const llm42_kv_cache* kv, 
 void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, int n, int k_padded,
                           const Workspace& ws, hipStream_t st) {
   ResidualEpi e{resid, n};
-  if (g_llm42_unconstrained && ws.m_pad > 64) launch_gemm<1>(w, x, n / 16, k_padded, n, ws, false, e, st);   // measurement only
+  // Off the fixed schedule (fast path, cost-of-determinism measurement) the split follows the batch,
+  // as in an ordinary engine: two halves while there are few rows to spread over the device, none beyond.
+  if (g_llm42_unconstrained && ws.m_rows > 16) launch_gemm<1>(w, x, n / 16, k_padded, n, ws, false, e, st);
   else launch_gemm<kSplit[GEMM_RESIDUAL]>(w, x, n / 16, k_padded, n, ws, false, e, st);
 }
 
