@@ -12,8 +12,9 @@ What it defines (paper sections in brackets):
   (one consistent token followed by T-1 candidates) is replayed through a
   decoder-only transformer in one causal pass, producing T output tokens and
   overwriting the window's KV-cache entries [§4.2 "Making KV cache consistent"];
-* the greedy sampler [§4.4 "Sampling"]: arg-max of the logits, lowest index
-  among equal maxima;
+* the sampler [§4.4 "Sampling"]: arg-max of the logits, lowest index among
+  equal maxima; for temperature > 0 the logits are first perturbed by Gumbel
+  noise that is a hash of (seed, request, position, vocabulary entry);
 * the commit / rollback rule [§4.2 Case-1, Case-2, "Guaranteed forward
   progress"]: accept the longest prefix of candidates that the verifier
   reproduces, plus the verifier's own token right after it, and truncate the
@@ -142,6 +143,58 @@ def greedy_argmax(logits: torch.Tensor) -> torch.Tensor:
     n = logits.shape[-1]
     idx = torch.arange(n, dtype=torch.int64).expand_as(logits)
     return torch.where(logits == vmax, idx, torch.full_like(idx, n)).min(dim=-1).values
+
+
+# --------------------------------------------------------------------------
+# seeded stochastic sampling [§4.4 "Sampling"]
+# --------------------------------------------------------------------------
+# The paper's sampler for temperature > 0 perturbs the logits with Gumbel noise that is a pure
+# function of a seed and of what is being sampled, and takes the arg-max; the same input and seed
+# always give the same token.  The paper does not give the hash; the reading taken here: the noise
+# of vocabulary entry v for the token that follows absolute position p of request r is
+#     u = (2 * (h >> 41) + 1) / 2^24  with  h = mix(mix(mix(seed ^ mix(r)) ^ p) ^ v),
+#     g = -log(-log(u)),
+# `mix` being the output function of the splitmix64 generator applied to its argument as state
+# (add the golden-ratio increment, two xor-shift-multiply rounds, a final xor-shift), all in
+# 64-bit unsigned arithmetic.  The token is argmax_v(logit_v / temperature + g_v), lowest index
+# among equal maxima.  Keying by the absolute position (not by the index inside a window) keeps
+# the sample independent of how positions are cut into windows.
+_M64 = (1 << 64) - 1
+
+
+def mix64(z):
+    """splitmix64 output function on numpy uint64 (wrapping arithmetic)."""
+    import numpy as np
+    z = np.asarray(z, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        z = z + np.uint64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+    return z ^ (z >> np.uint64(31))
+
+
+def gumbel_noise(seed: int, request_id: int, position: int, vocab: int):
+    """float64 Gumbel noise for every vocabulary entry of one (request, position)."""
+    import numpy as np
+    k1 = mix64(np.uint64(seed & _M64) ^ mix64(np.uint64(request_id & _M64)))
+    k2 = mix64(k1 ^ np.uint64(position))
+    h = mix64(k2 ^ np.arange(vocab, dtype=np.uint64))
+    u = (2.0 * (h >> np.uint64(41)).astype(np.float64) + 1.0) / float(1 << 24)
+    return -np.log(-np.log(u))
+
+
+def sample_tokens(logits: torch.Tensor, temperature: float, seed: int, request_id: int,
+                  positions: Sequence[int]):
+    """One token per row of `logits` ([rows, vocab]); row i belongs to absolute position positions[i].
+    temperature == 0 is the greedy sampler.  Returns (tokens, perturbed logits or None)."""
+    if temperature == 0:
+        return greedy_argmax(logits), None
+    import numpy as np
+    noisy = torch.empty_like(logits, dtype=torch.float64)
+    for i, p in enumerate(positions):
+        g = gumbel_noise(seed, request_id, int(p), logits.shape[-1])
+        noisy[i] = logits[i].double() / float(temperature) + torch.from_numpy(g)
+    return greedy_argmax(noisy), noisy
 
 
 # --------------------------------------------------------------------------
