@@ -180,6 +180,33 @@ llm42_status llm42_commit_rollback(
     int32_t*       rolled_back_counts,  /* dev [num_seqs] or NULL, out       */
     void*          hip_stream);
 
+/* Seeded stochastic sampling (SS 4.4 "Sampling": for temperature > 0 the logits are perturbed with
+ * Gumbel noise generated by a seeded hash, so that the same input and seed always give the same token).
+ * With temperature > 0 the token of a row is  argmax_v( logit_v / temperature + g_v ),  lowest index
+ * on ties, where g_v = -log(-log(u_v)), u_v = (2 * (h >> 41) + 1) / 2^24 and
+ * h = mix(mix(mix(seed ^ mix(request_id)) ^ position) ^ v);  mix is the output function of the
+ * splitmix64 generator applied to its argument (add 0x9E3779B97F4A7C15; xor-shift 30, multiply
+ * 0xBF58476D1CE4E5B9; xor-shift 27, multiply 0x94D049BB133111EB; xor-shift 31), position is the
+ * row's absolute position in its sequence and request_id the caller's id of the sequence.
+ * temperature == 0 (or a NULL llm42_sampling) is the greedy sampler.  out_logits, if asked for,
+ * always receives the unperturbed logits. */
+typedef struct {
+  float          temperature;         /* >= 0                                             */
+  uint64_t       seed;
+  const int64_t* request_ids;         /* dev [num_seqs]; NULL: the index in the call      */
+} llm42_sampling;
+
+/* llm42_verify_window / llm42_decode_step with the sampler above in place of the arg-max. */
+llm42_status llm42_verify_window_sampled(
+    const llm42_model* model, const llm42_kv_cache* kv_cache, const int32_t* seq_lens, const int32_t* candidates,
+    int32_t window, const int32_t* n_valid, int32_t num_seqs, int32_t max_context, int32_t* out_tokens,
+    int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids, int32_t n_dump,
+    void* workspace, size_t workspace_bytes, void* hip_stream, const llm42_sampling* sampling);
+llm42_status llm42_decode_step_sampled(
+    const llm42_model* model, const llm42_kv_cache* kv_cache, const int32_t* seq_lens, const int32_t* tokens,
+    int32_t num_seqs, int32_t max_context, int32_t* out_tokens, int32_t* seq_status,
+    void* workspace, size_t workspace_bytes, void* hip_stream, const llm42_sampling* sampling);
+
 /* Fast path (SS 4.1: candidate tokens come from ordinary, high-throughput decoding whose reduction
  * order follows the batch): one greedy decoding step for num_seqs sequences.  tokens[s] is the input
  * token of sequence s at position seq_lens[s]; its K and V are written to that slot of the cache

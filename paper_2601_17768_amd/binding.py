@@ -24,7 +24,8 @@ LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
            "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
-           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained", "llm42_decode_step")
+           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained", "llm42_decode_step", "llm42_verify_window_sampled",
+           "llm42_decode_step_sampled")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
                   "argmax", "commit")
 
@@ -46,6 +47,15 @@ class Weights(ctypes.Structure):
     _fields_ = [("embed", ctypes.c_void_p), ("final_norm", ctypes.c_void_p), ("lm_head", ctypes.c_void_p)] + \
                [(n, ctypes.POINTER(ctypes.c_void_p)) for n in
                 ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+
+
+class Sampling(ctypes.Structure):
+    _fields_ = [("temperature", ctypes.c_float), ("seed", ctypes.c_uint64), ("request_ids", ctypes.c_void_p)]
+
+
+def make_sampling(temperature: float, seed: int, request_ids: Optional[torch.Tensor] = None) -> Sampling:
+    """request_ids: int64 device tensor [num_seqs] or None (then the index in the call is the id)."""
+    return Sampling(float(temperature), int(seed) & ((1 << 64) - 1), _ptr(request_ids, torch.int64))
 
 
 class KVCache(ctypes.Structure):
@@ -77,8 +87,12 @@ def load_library(path: Optional[str] = None):
     lib.llm42_verify_window.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, i32,
                                         vp, ctypes.c_size_t, vp]
     lib.llm42_verify_window.restype = i32
+    lib.llm42_verify_window_sampled.argtypes = lib.llm42_verify_window.argtypes + [ctypes.POINTER(Sampling)]
+    lib.llm42_verify_window_sampled.restype = i32
     lib.llm42_decode_step.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.llm42_decode_step.restype = i32
+    lib.llm42_decode_step_sampled.argtypes = lib.llm42_decode_step.argtypes + [ctypes.POINTER(Sampling)]
+    lib.llm42_decode_step_sampled.restype = i32
     lib.llm42_commit_rollback.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.llm42_commit_rollback.restype = i32
     lib.llm42_profile_enable.argtypes = [i32, i32]
@@ -164,7 +178,8 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
                         n_valid: Optional[torch.Tensor], max_context: int, out_tokens: torch.Tensor,
                         workspace: torch.Tensor, seq_status: Optional[torch.Tensor] = None,
                         out_logits: Optional[torch.Tensor] = None, dump_seq_ids: Optional[torch.Tensor] = None,
-                        stream=None) -> None:
+                        stream=None, sampling: Optional[Sampling] = None) -> None:
+    """sampling given: llm42_verify_window_sampled."""
     num_seqs = seq_lens.numel()
     if candidates.shape != (num_seqs, window) or out_tokens.shape != (num_seqs, window):
         raise ValueError("candidates / out_tokens must be [num_seqs, window]")
@@ -174,24 +189,32 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
     if n_dump and (out_logits is None or out_logits.shape[0] != n_dump or out_logits.shape[1] != window):
         raise ValueError("out_logits must be [n_dump, window, vocab]")
     kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
-    _check(load_library().llm42_verify_window(
-        model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(candidates, torch.int32), window,
-        _ptr(n_valid, torch.int32), num_seqs, max_context, _ptr(out_tokens, torch.int32),
-        _ptr(seq_status, torch.int32), _ptr(out_logits, torch.float32), _ptr(dump_seq_ids, torch.int32), n_dump,
-        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+    args = (model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(candidates, torch.int32), window,
+            _ptr(n_valid, torch.int32), num_seqs, max_context, _ptr(out_tokens, torch.int32),
+            _ptr(seq_status, torch.int32), _ptr(out_logits, torch.float32), _ptr(dump_seq_ids, torch.int32), n_dump,
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if sampling is None:
+        _check(load_library().llm42_verify_window(*args))
+    else:
+        _check(load_library().llm42_verify_window_sampled(*args, ctypes.byref(sampling)))
 
 
 def llm42_decode_step(model: int, kv_base: torch.Tensor, num_blocks: int, block_table: torch.Tensor,
                       seq_lens: torch.Tensor, tokens: torch.Tensor, max_context: int, out_tokens: torch.Tensor,
-                      workspace: torch.Tensor, seq_status: Optional[torch.Tensor] = None, stream=None) -> None:
+                      workspace: torch.Tensor, seq_status: Optional[torch.Tensor] = None, stream=None,
+                      sampling: Optional[Sampling] = None) -> None:
+    """sampling given: llm42_decode_step_sampled."""
     num_seqs = seq_lens.numel()
     if tokens.numel() != num_seqs or out_tokens.numel() != num_seqs:
         raise ValueError("tokens / out_tokens must hold one entry per sequence")
     kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
-    _check(load_library().llm42_decode_step(
-        model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(tokens, torch.int32), num_seqs, max_context,
-        _ptr(out_tokens, torch.int32), _ptr(seq_status, torch.int32), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+    args = (model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(tokens, torch.int32), num_seqs, max_context,
+            _ptr(out_tokens, torch.int32), _ptr(seq_status, torch.int32), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if sampling is None:
+        _check(load_library().llm42_decode_step(*args))
+    else:
+        _check(load_library().llm42_decode_step_sampled(*args, ctypes.byref(sampling)))
 
 
 def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_valid: Optional[torch.Tensor],

@@ -262,6 +262,18 @@ llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv,
                                  int32_t max_context, int32_t* out_tokens, int32_t* seq_status, float* out_logits,
                                  const int32_t* dump_seq_ids, int32_t n_dump, void* workspace, size_t workspace_bytes,
                                  void* hip_stream) {
+  return llm42_verify_window_sampled(m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context, out_tokens,
+                                     seq_status, out_logits, dump_seq_ids, n_dump, workspace, workspace_bytes,
+                                     hip_stream, nullptr);
+}
+
+llm42_status llm42_verify_window_sampled(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                                         const int32_t* candidates, int32_t window, const int32_t* n_valid,
+                                         int32_t num_seqs, int32_t max_context, int32_t* out_tokens,
+                                         int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids,
+                                         int32_t n_dump, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                         const llm42_sampling* sampling) {
+  if (sampling && !(sampling->temperature >= 0.f)) return fail(LLM42_EINVAL, "verify_window: negative temperature");
   if (!m || !kv || !seq_lens || !candidates || !out_tokens || !workspace)
     return fail(LLM42_EINVAL, "verify_window: null argument");
   if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
@@ -298,7 +310,7 @@ llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv,
     TIMED(LLM42_K_DOWN, launch_gemm_residual(ly.wdown, ws.hidden, ws.resid, c.d_model, m->ffn_k, ws, st));
   }
   TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, m->final_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
-  TIMED(LLM42_K_LM_HEAD, launch_gemm_logits(m, window, n_dump > 0 ? out_logits : nullptr, ws, st));
+  TIMED(LLM42_K_LM_HEAD, launch_gemm_logits(m, window, n_dump > 0 ? out_logits : nullptr, sampling, ws, st));
   TIMED(LLM42_K_ARGMAX, launch_argmax_merge(m, num_seqs, window, out_tokens, ws, st));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(LLM42_EHIP, "verify_window: launch failed: %s", hipGetErrorString(e));
@@ -308,10 +320,19 @@ llm42_status llm42_verify_window(const llm42_model* m, const llm42_kv_cache* kv,
 llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
                                const int32_t* tokens, int32_t num_seqs, int32_t max_context, int32_t* out_tokens,
                                int32_t* seq_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return llm42_decode_step_sampled(m, kv, seq_lens, tokens, num_seqs, max_context, out_tokens, seq_status, workspace,
+                                   workspace_bytes, hip_stream, nullptr);
+}
+
+llm42_status llm42_decode_step_sampled(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                                       const int32_t* tokens, int32_t num_seqs, int32_t max_context,
+                                       int32_t* out_tokens, int32_t* seq_status, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream, const llm42_sampling* sampling) {
   const int saved = g_llm42_unconstrained;
   g_llm42_unconstrained = 1;
-  const llm42_status st = llm42_verify_window(m, kv, seq_lens, tokens, 1, nullptr, num_seqs, max_context, out_tokens,
-                                              seq_status, nullptr, nullptr, 0, workspace, workspace_bytes, hip_stream);
+  const llm42_status st =
+      llm42_verify_window_sampled(m, kv, seq_lens, tokens, 1, nullptr, num_seqs, max_context, out_tokens, seq_status,
+                                  nullptr, nullptr, 0, workspace, workspace_bytes, hip_stream, sampling);
   g_llm42_unconstrained = saved;
   return st;
 }

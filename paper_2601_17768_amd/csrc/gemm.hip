@@ -132,15 +132,32 @@ struct LogitsEpi {
   float* out_logits;   // [n_dump][window][vocab] or null
   float2* amax;        // [m_pad][n_blocks]
   int window, vocab, n_blocks;
+  // seeded sampling: 1 / temperature (0: greedy), seed, the caller's request ids (or null)
+  float inv_temp;
+  uint64_t seed;
+  const int64_t* request_ids;
   struct Row {
     int pos, s, slot;
+    uint64_t key;      // hash of (seed, request, position): the row's noise stream
   };
   typedef Row Pre;
+  // output function of the splitmix64 generator
+  static __device__ inline uint64_t mix(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+  }
   __device__ Row row_info(int row) const {
     Row p;
     p.pos = row_pos[row];
     p.s = row_seq[row];
     p.slot = out_logits ? dump_slot[p.s] : -1;
+    p.key = 0;
+    if (inv_temp != 0.f) {
+      const uint64_t rid = request_ids ? (uint64_t)request_ids[p.s] : (uint64_t)p.s;
+      p.key = mix(mix(seed ^ mix(rid)) ^ (uint64_t)(uint32_t)max(p.pos, 0));
+    }
     return p;
   }
   __device__ Pre pre(int, int, int, const Row& r) const { return r; }
@@ -151,12 +168,22 @@ struct LogitsEpi {
       if (slot >= 0)
         *(f32x4*)(out_logits + ((size_t)slot * window + (row - s * window)) * vocab + n0) = acc;
     }
+    // what the sampler ranks: the logits, or (temperature > 0) logit / temperature + Gumbel noise
+    f32x4 val = acc;
+    if (inv_temp != 0.f) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint64_t h = mix(p.key ^ (uint64_t)(n0 + e));
+        const float u = (float)(2u * (uint32_t)(h >> 41) + 1u) * 0x1p-24f;   // exact: 24 significant bits, in (0, 1)
+        val[e] = acc[e] * inv_temp - logf(-logf(u));
+      }
+    }
     // best of this lane's 4 features (ascending index, strict '>' keeps the lowest on ties) ...
-    float bv = acc[0];
+    float bv = val[0];
     int bi = n0;
 #pragma unroll
     for (int e = 1; e < 4; ++e)
-      if (acc[e] > bv) { bv = acc[e]; bi = n0 + e; }
+      if (val[e] > bv) { bv = val[e]; bi = n0 + e; }
     // ... then of the 4 lanes that hold the token's other features of this block
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
@@ -611,7 +638,8 @@ void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hi
   launch_gemm<kSplit[GEMM_GATE_UP]>(m->layers[layer].wgu, ws.normed, m->gu_blocks, m->cfg.d_model, m->gu_blocks * 16, ws, true, e, st);
 }
 
-void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const Workspace& ws, hipStream_t st) {
+void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const llm42_sampling* sampling,
+                        const Workspace& ws, hipStream_t st) {
   LogitsEpi e;
   e.row_pos = ws.row_pos;
   e.row_seq = ws.row_seq;
@@ -621,5 +649,9 @@ void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, con
   e.window = window;
   e.vocab = m->cfg.vocab;
   e.n_blocks = m->cfg.vocab / 16;
+  const bool sampled = sampling && sampling->temperature > 0.f;
+  e.inv_temp = sampled ? 1.0f / sampling->temperature : 0.f;
+  e.seed = sampled ? sampling->seed : 0;
+  e.request_ids = sampled ? sampling->request_ids : nullptr;
   launch_gemm<kSplit[GEMM_LOGITS]>(m->lm_head, ws.normed, m->cfg.vocab / 16, m->cfg.d_model, m->cfg.vocab, ws, true, e, st);
 }

@@ -128,7 +128,8 @@ void launch_gemm_qkv(const llm42_model* m, int layer, const llm42_kv_cache* kv, 
 void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, int n, int k_padded,
                           const Workspace& ws, hipStream_t st);
 void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hipStream_t st);
-void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const Workspace& ws, hipStream_t st);
+void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const llm42_sampling* sampling,
+                        const Workspace& ws, hipStream_t st);
 
 // Measurement only (llm42_measure_unconstrained): the reduction schedule may then follow the batch.
 extern int g_llm42_unconstrained;

@@ -35,11 +35,12 @@ class DvrStats:
 
 
 def generate(sess: VerifierSession, kv: torch.Tensor, block_table: torch.Tensor, seq_lens: torch.Tensor,
-             first_tokens: torch.Tensor, max_new: int, window: int):
+             first_tokens: torch.Tensor, max_new: int, window: int, sampling=None):
     """Runs the loop until every sequence has at least max_new committed tokens.
 
     seq_lens (int32 [B], device) is advanced in place; first_tokens (int32 [B]) are the consistent
-    tokens T_0 whose K/V are not yet cached.  Returns (tokens [B, max_new] on the host, DvrStats).
+    tokens T_0 whose K/V are not yet cached.  `sampling` (binding.Sampling or None = greedy) is
+    used by the fast path and by the verifier alike.  Returns (tokens [B, max_new] on the host, DvrStats).
     The cache must have room for seq_lens + max_new + 2 * window positions per sequence."""
     if window < 2:
         raise ValueError("the loop needs at least one candidate per window")
@@ -64,12 +65,14 @@ def generate(sess: VerifierSession, kv: torch.Tensor, block_table: torch.Tensor,
         fast_lens = seq_lens.clone()
         cur = t0.clone()
         for i in range(1, window):
-            B.llm42_decode_step(sess.model, kv, num_blocks, block_table, fast_lens, cur, max_context, nxt, ws)
+            B.llm42_decode_step(sess.model, kv, num_blocks, block_table, fast_lens, cur, max_context, nxt, ws,
+                                sampling=sampling)
             cand[:, i] = nxt
             cur = nxt.clone()
             fast_lens += 1
         # 2. verifier, 3. commit
-        B.llm42_verify_window(sess.model, kv, num_blocks, block_table, seq_lens, cand, window, None, max_context, out, ws)
+        B.llm42_verify_window(sess.model, kv, num_blocks, block_table, seq_lens, cand, window, None, max_context, out, ws,
+                              sampling=sampling)
         B.llm42_commit_rollback(cand, out, None, seq_lens, counts, ctoks, rolled)
         t0 = ctoks[rows, (counts - 1).long()].clone()      # the corrected (or next) token: consistent by construction
         c_host, t_host, r_host = counts.cpu().tolist(), ctoks.cpu().tolist(), rolled.cpu().tolist()
@@ -86,7 +89,7 @@ def generate(sess: VerifierSession, kv: torch.Tensor, block_table: torch.Tensor,
 
 
 def generate_verifier_only(sess: VerifierSession, kv: torch.Tensor, block_table: torch.Tensor,
-                           seq_lens: torch.Tensor, first_tokens: torch.Tensor, max_new: int):
+                           seq_lens: torch.Tensor, first_tokens: torch.Tensor, max_new: int, sampling=None):
     """The reference the loop must reproduce: one token at a time through the verifier alone
     (fixed schedule for every token; what the paper calls running everything deterministically)."""
     dev = sess.device
@@ -98,7 +101,8 @@ def generate_verifier_only(sess: VerifierSession, kv: torch.Tensor, block_table:
     out = torch.empty((n_seq, 1), dtype=torch.int32, device=dev)
     toks = []
     for _ in range(max_new):
-        B.llm42_verify_window(sess.model, kv, num_blocks, block_table, seq_lens, cur, 1, None, max_context, out, ws)
+        B.llm42_verify_window(sess.model, kv, num_blocks, block_table, seq_lens, cur, 1, None, max_context, out, ws,
+                              sampling=sampling)
         seq_lens += 1
         toks.append(out[:, 0].clone())
         cur = out.clone()

@@ -59,8 +59,9 @@ class VerifierSession:
                candidates: torch.Tensor, n_valid: Optional[torch.Tensor] = None,
                dump_seq_ids: Optional[torch.Tensor] = None, max_context: Optional[int] = None,
                out_tokens: Optional[torch.Tensor] = None, out_logits: Optional[torch.Tensor] = None,
-               seq_status: Optional[torch.Tensor] = None):
-        """One llm42_verify_window call.  Returns (out_tokens, seq_status, out_logits)."""
+               seq_status: Optional[torch.Tensor] = None, sampling=None):
+        """One llm42_verify_window call (llm42_verify_window_sampled if `sampling`, a binding.Sampling,
+        is given).  Returns (out_tokens, seq_status, out_logits)."""
         num_seqs, window = candidates.shape
         if max_context is None:
             max_context = block_table.shape[1] * B.LLM42_KV_BLOCK
@@ -73,7 +74,7 @@ class VerifierSession:
             out_logits = torch.zeros((dump_seq_ids.numel(), window, self.shape.vocab), dtype=torch.float32,
                                      device=self.device)
         B.llm42_verify_window(self.model, kv, kv.shape[2], block_table, seq_lens, candidates, window, n_valid,
-                              max_context, out_tokens, ws, seq_status, out_logits, dump_seq_ids)
+                              max_context, out_tokens, ws, seq_status, out_logits, dump_seq_ids, sampling=sampling)
         return out_tokens, seq_status, out_logits
 
     def commit(self, candidates: torch.Tensor, out_tokens: torch.Tensor, seq_lens: torch.Tensor,
