@@ -420,7 +420,7 @@ template <int WBN, int WBM, int NST, int WGS, bool ADD_PARTIAL, class Epi>
 __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
                                                          const float* __restrict__ partial, int n, int tiles_n,
-                                                         int tiles_m, Epi epi) {
+                                                         int tiles_m, int sm_tiles, Epi epi) {
   constexpr int TBN = 2 * WBN, TBM = 2 * WBM;   // 16-row blocks per tile side (features, tokens)
   constexpr int ST = TBN + TBM;                 // operand tiles per stage of one k-tile (weights then activations)
   constexpr int PW = ST / 4;                    // operand tiles each wave fetches per stage
@@ -432,12 +432,14 @@ __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __re
   const int wn = wave >> 1, wm = wave & 1;
   // XCD-aware numbering.  Workgroup ids are dealt round-robin to the 8 XCDs; the 32 workgroups that
   // run together on one XCD (consecutive ids of that XCD) form a super-tile of SN feature tiles x SM
-  // token tiles, so that per k-step the XCD's L2 fetches SN weight tiles + SM activation tiles for
-  // SN*SM workgroups.  Super-tiles are dealt to the XCDs round-robin.
-  constexpr int SN = 4, SM = 8;
+  // token tiles (SN * SM = 32), so that per k-step the XCD's L2 fetches SN weight tiles + SM activation
+  // tiles for 32 workgroups.  Super-tiles are dealt to the XCDs round-robin.  SM follows the number of
+  // token tiles (1, 2, 4 or 8): a workgroup without a tile still has to wait for a CU with free LDS
+  // before it can leave, so holes in the numbering are expensive.
+  const int SM = sm_tiles, SN = 32 / sm_tiles;
   const int sup_n = (tiles_n + SN - 1) / SN, sup_m = (tiles_m + SM - 1) / SM;
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int sup = (local / (SN * SM)) * 8 + xcd, in_sup = local % (SN * SM);
+  const int sup = (local >> 5) * 8 + xcd, in_sup = local & 31;
   if (sup >= sup_n * sup_m) return;
   const int tn = (sup / sup_m) * SN + in_sup / SM, tm = (sup % sup_m) * SM + in_sup % SM;
   if (tn >= tiles_n || tm >= tiles_m) return;
@@ -542,18 +544,19 @@ template <int WBN, int WBM, int NST, int WGS, int SPLIT, class Epi>
 void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles, int n, const Workspace& ws,
                   const Epi& epi, hipStream_t st) {
   const int tiles_n = (n_blocks + 2 * WBN - 1) / (2 * WBN), tiles_m = ws.m_pad / (32 * WBM);
-  const int supers = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);      // super-tiles of 4 x 8 tiles, 8 XCDs
+  const int sm = tiles_m >= 8 ? 8 : tiles_m >= 4 ? 4 : tiles_m >= 2 ? 2 : 1, sn = 32 / sm;   // super-tiles of sn x sm tiles
+  const int supers = ((tiles_n + sn - 1) / sn) * ((tiles_m + sm - 1) / sm);
   const unsigned grid = 8u * 32u * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
     gemm_tiled_kernel<WBN, WBM, NST, WGS, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr,
-                                                                            n, tiles_n, tiles_m, epi);
+                                                                            n, tiles_n, tiles_m, sm, epi);
   } else {
     const int h = split_point(k_tiles);
     StorePartialEpi pe{ws.split_part, n};
     gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi><<<grid, 256, 0, st>>>(
-        wp, xp, n_blocks, k_tiles, h, k_tiles - h, nullptr, n, tiles_n, tiles_m, pe);
+        wp, xp, n_blocks, k_tiles, h, k_tiles - h, nullptr, n, tiles_n, tiles_m, sm, pe);
     gemm_tiled_kernel<WBN, WBM, NST, WGS, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part,
-                                                                           n, tiles_n, tiles_m, epi);
+                                                                           n, tiles_n, tiles_m, sm, epi);
   }
 }
 
@@ -597,8 +600,12 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
   const long long big_tiles = (long long)((n_blocks + 7) / 8) * (m_pad / 256);
   if (m_pad >= 512 && m_pad % 256 == 0 && big_tiles >= 2LL * ws.num_cus)
     launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
-  else
+  else if ((long long)((n_blocks + 7) / 8) * (m_pad / 128) >= 2LL * ws.num_cus)
     launch_tiled<4, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  else
+    // fewer workgroups than the device has room for: the launch is bound by how fast each workgroup can
+    // stream its operands, i.e. by the bytes it keeps in flight - a ring of 8 stages instead of 4
+    launch_tiled<4, 4, 8, 1, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
 }
 
 }  // namespace
