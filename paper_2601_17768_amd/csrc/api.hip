@@ -111,7 +111,7 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.attn_items = (int4*)take(sizeof(int4) * (size_t)num_seqs * ws.attn_units);
   ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (1 + c.n_layers));
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
-  ws.split_part = (float*)take(ws.m_pad > 64 ? 4ull * ws.m_pad * c.d_model : 0);
+  ws.split_part = (float*)take(ws.m_pad > 64 ? 2 * 4ull * ws.m_pad * c.d_model : 0);
   ws.bytes = off;
   return ws;
 }

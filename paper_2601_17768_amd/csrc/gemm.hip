@@ -203,10 +203,12 @@ struct LogitsEpi {
 // ---------------------------------------------------------------------------------------------
 __host__ __device__ inline int split_point(int k_tiles) { return (k_tiles + 1) / 2; }
 
-// fp32 partial of one k-half of a split GEMM (large-batch path: the halves are two launches).
+// fp32 partial of one k-half of a split GEMM (large-batch path: the halves are two launches, or the
+// two y-planes of one launch, each with a buffer of its own).
 struct StorePartialEpi {
   float* partial;   // [m_pad][n] in the residual-stream layout
   int n;
+  size_t plane;     // distance (floats) from the first half's buffer to the second's
   struct Row {};
   struct Pre {};
   __device__ Row row_info(int) const { return Row{}; }
@@ -420,7 +422,7 @@ template <int WBN, int WBM, int NST, int WGS, bool ADD_PARTIAL, class Epi>
 __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
                                                          const float* __restrict__ partial, int n, int tiles_n,
-                                                         int tiles_m, int sm_tiles, Epi epi) {
+                                                         int tiles_m, int sm_tiles, int group_tiles, int planes, Epi epi) {
   constexpr int TBN = 2 * WBN, TBM = 2 * WBM;   // 16-row blocks per tile side (features, tokens)
   constexpr int ST = TBN + TBM;                 // operand tiles per stage of one k-tile (weights then activations)
   constexpr int PW = ST / 4;                    // operand tiles each wave fetches per stage
@@ -430,20 +432,30 @@ __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __re
   // wave index as a scalar, so that everything derived from it (operand addresses) stays in SGPRs
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wn = wave >> 1, wm = wave & 1;
-  // XCD-aware numbering.  Workgroup ids are dealt round-robin to the 8 XCDs; the 32 workgroups that
-  // run together on one XCD (consecutive ids of that XCD) form a super-tile of SN feature tiles x SM
-  // token tiles (SN * SM = 32), so that per k-step the XCD's L2 fetches SN weight tiles + SM activation
-  // tiles for 32 workgroups.  Super-tiles are dealt to the XCDs round-robin.  SM follows the number of
-  // token tiles (1, 2, 4 or 8): a workgroup without a tile still has to wait for a CU with free LDS
-  // before it can leave, so holes in the numbering are expensive.
-  const int SM = sm_tiles, SN = 32 / sm_tiles;
+  // XCD-aware numbering.  Workgroup ids are dealt round-robin to the 8 XCDs; G consecutive ids of one
+  // XCD form a super-tile of SN feature tiles x SM token tiles (SN * SM = G), so that per k-step the
+  // XCD's L2 fetches SN weight tiles + SM activation tiles for G workgroups.  Super-tiles are dealt
+  // to the XCDs round-robin; the two k-halves of a side-by-side split are numbered one after the other.
+  // G is 32 when that still gives every XCD a super-tile, less for small launches; SM follows the
+  // number of token tiles.  (A workgroup without a tile still has to wait for a CU with free LDS
+  // before it can leave, so holes in the numbering are expensive.)
+  const int G = group_tiles, SM = sm_tiles, SN = G / SM;
   const int sup_n = (tiles_n + SN - 1) / SN, sup_m = (tiles_m + SM - 1) / SM;
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int sup = (local >> 5) * 8 + xcd, in_sup = local & 31;
-  if (sup >= sup_n * sup_m) return;
+  const int sup_all = (local / G) * 8 + xcd, in_sup = local % G;
+  const int plane = sup_all / (sup_n * sup_m), sup = sup_all % (sup_n * sup_m);
+  if (plane >= planes) return;
   const int tn = (sup / sup_m) * SN + in_sup / SM, tm = (sup % sup_m) * SM + in_sup % SM;
   if (tn >= tiles_n || tm >= tiles_m) return;
   const int n0 = tn * TBN, m0 = tm * TBM;      // first feature / token block of the tile
+  if constexpr (std::is_same<Epi, StorePartialEpi>::value) {
+    // both halves of a split GEMM in one launch: plane 1 takes the k-tiles after the first k_count
+    if (plane) {
+      k_begin = k_count;
+      k_count = k_tiles - k_count;
+      epi.partial += epi.plane;
+    }
+  }
 
   // Operand tiles go from global memory straight into LDS (no staging registers, no LDS stores):
   // per stage this wave moves PW tiles of 1 KiB, lane i's 16 bytes landing at tile base + 16 i.
@@ -537,26 +549,56 @@ __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __re
         epi(nb, lane, row, v, epi.pre(nb, lane, row, ri));
       }
     }
+    __builtin_amdgcn_sched_barrier(0);   // one token block at a time: hoisting the next blocks' loads up here costs spills
   }
 }
 
+// p0 + p1 of a split GEMM whose halves ran side by side, handed to the GEMM's epilogue with the
+// same (feature block, lane, row) ownership as in the GEMM kernels: one wave per 16 x 16 block.
+template <class Epi>
+__global__ __launch_bounds__(256) void split_combine_kernel(const float* __restrict__ p0, const float* __restrict__ p1,
+                                                            int n_blocks, int n, Epi epi) {
+  const int lane = threadIdx.x & 63;
+  const int nb = blockIdx.x * 4 + (threadIdx.x >> 6), row = blockIdx.y * 16 + (lane & 15);
+  if (nb >= n_blocks) return;
+  const size_t off = resid_off(row, nb * 16 + (lane >> 4) * 4, n);
+  const typename Epi::Pre pre = epi.pre(nb, lane, row, epi.row_info(row));
+  const f32x4 v = *(const f32x4*)(p0 + off) + *(const f32x4*)(p1 + off);
+  epi(nb, lane, row, v, pre);
+}
+
+// side_by_side (split GEMMs only): both k-halves in one launch of twice the workgroups plus a small
+// combining pass, instead of two launches one after the other - for launches that do not fill the
+// device by themselves.  The arithmetic per output element is the same either way.
 template <int WBN, int WBM, int NST, int WGS, int SPLIT, class Epi>
 void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles, int n, const Workspace& ws,
-                  const Epi& epi, hipStream_t st) {
+                  const Epi& epi, hipStream_t st, bool side_by_side = false) {
   const int tiles_n = (n_blocks + 2 * WBN - 1) / (2 * WBN), tiles_m = ws.m_pad / (32 * WBM);
-  const int sm = tiles_m >= 8 ? 8 : tiles_m >= 4 ? 4 : tiles_m >= 2 ? 2 : 1, sn = 32 / sm;   // super-tiles of sn x sm tiles
-  const int supers = ((tiles_n + sn - 1) / sn) * ((tiles_m + sm - 1) / sm);
-  const unsigned grid = 8u * 32u * (unsigned)((supers + 7) / 8);
+  const int planes = SPLIT == 2 && side_by_side ? 2 : 1;
+  // super-tiles of g = sn x sm tiles (see the kernel): at least one per XCD if the launch has 32 tiles or more
+  const int tiles = tiles_n * tiles_m * planes;
+  const int g = tiles >= 256 ? 32 : tiles >= 128 ? 16 : tiles >= 64 ? 8 : 4;
+  const int sm = tiles_m >= 8 ? (g < 8 ? g : 8) : tiles_m >= 4 ? 4 : tiles_m >= 2 ? 2 : 1, sn = g / sm;
+  const int supers = ((tiles_n + sn - 1) / sn) * ((tiles_m + sm - 1) / sm) * planes;
+  const unsigned grid = 8u * (unsigned)g * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
     gemm_tiled_kernel<WBN, WBM, NST, WGS, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr,
-                                                                            n, tiles_n, tiles_m, sm, epi);
-  } else {
-    const int h = split_point(k_tiles);
-    StorePartialEpi pe{ws.split_part, n};
+                                                                            n, tiles_n, tiles_m, sm, g, 1, epi);
+    return;
+  }
+  const int h = split_point(k_tiles);
+  const size_t plane = (size_t)ws.m_pad * n;
+  StorePartialEpi pe{ws.split_part, n, plane};
+  if (side_by_side) {
     gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi><<<grid, 256, 0, st>>>(
-        wp, xp, n_blocks, k_tiles, h, k_tiles - h, nullptr, n, tiles_n, tiles_m, sm, pe);
+        wp, xp, n_blocks, k_tiles, 0, h, nullptr, n, tiles_n, tiles_m, sm, g, 2, pe);
+    split_combine_kernel<Epi><<<dim3((n_blocks + 3) / 4, ws.m_pad / 16), 256, 0, st>>>(ws.split_part, ws.split_part + plane,
+                                                                                      n_blocks, n, epi);
+  } else {
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi><<<grid, 256, 0, st>>>(
+        wp, xp, n_blocks, k_tiles, h, k_tiles - h, nullptr, n, tiles_n, tiles_m, sm, g, 1, pe);
     gemm_tiled_kernel<WBN, WBM, NST, WGS, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part,
-                                                                           n, tiles_n, tiles_m, sm, epi);
+                                                                           n, tiles_n, tiles_m, sm, g, 1, epi);
   }
 }
 
@@ -595,17 +637,26 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
     }
     return;
   }
-  // more than 64 tokens: m_pad is a multiple of 128 (up to 512 rows) or of 256 (beyond)
-  // 128 x 256 tiles when they fill the device (two workgroups per CU) at least once, else 128 x 128
-  const long long big_tiles = (long long)((n_blocks + 7) / 8) * (m_pad / 256);
-  if (m_pad >= 512 && m_pad % 256 == 0 && big_tiles >= 2LL * ws.num_cus)
-    launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
-  else if ((long long)((n_blocks + 7) / 8) * (m_pad / 128) >= 2LL * ws.num_cus)
-    launch_tiled<4, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+  // More than 64 tokens: m_pad is a multiple of 128 (up to 512 rows) or of 256 (beyond).  Larger tiles
+  // move fewer operand bytes per flop, smaller ones give more workgroups; measured over 128 .. 4096 rows
+  // of the 8B shapes, the best choice is the largest tile that still yields about as many workgroups as
+  // the device has CUs.  Where the epilogue is heavy (rotary embedding and cache writes) the 128 x 256
+  // tile waits until it fills the device, since its epilogues overlap less with other workgroups' main
+  // loops; the LM head never takes it.  A split GEMM runs its halves side by side unless each half
+  // fills the device by itself.
+  const long long cus = ws.num_cus;
+  const long long t256 = m_pad % 256 == 0 ? (long long)((n_blocks + 7) / 8) * (m_pad / 256) : 0;
+  const long long t128 = (long long)((n_blocks + 7) / 8) * (m_pad / 128);
+  const bool side_by_side = SPLIT == 2 && t256 < 2 * cus;
+  const int p = side_by_side ? 2 : 1;
+  constexpr bool kLogits = std::is_same<Epi, LogitsEpi>::value, kQkv = std::is_same<Epi, QkvEpi>::value;
+  const bool big = !kLogits && (kQkv ? t256 >= 2 * cus : t256 * p * 5 >= 4 * cus);
+  if (big)
+    launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st, side_by_side);
+  else if (t128 * p * 4 >= 3 * cus)
+    launch_tiled<4, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st, side_by_side);
   else
-    // fewer workgroups than the device has room for: the launch is bound by how fast each workgroup can
-    // stream its operands, i.e. by the bytes it keeps in flight - a ring of 8 stages instead of 4
-    launch_tiled<4, 4, 8, 1, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st);
+    launch_tiled<2, 4, 12, 1, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st, side_by_side);
 }
 
 }  // namespace
