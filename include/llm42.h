@@ -221,6 +221,42 @@ llm42_status llm42_decode_step(
     int32_t num_seqs, int32_t max_context, int32_t* out_tokens, int32_t* seq_status,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Deterministic prefill (SS 4.1, use of observation O3: prefill is made deterministic by itself, without
+ * a verifier; SS 4.2: the first output token T_0 comes from it.  The limitations paragraph that closes
+ * SS 5 says the prototype cannot share prefix caches because its prefill and its decoding reduce
+ * differently; here prefill IS the verifier run over the prompt, and the
+ * verifier's result at a position depends on the tokens up to it only, never on how they were cut
+ * into passes or batched, so a cached prefix can be shared).  For every sequence s the tokens
+ * prompt_tokens[prompt_offsets[s] .. prompt_offsets[s+1]) are appended behind the seq_lens[s]
+ * positions that its block table already holds (0 for a fresh sequence; the length of a shared or
+ * previously cached prefix otherwise): the call runs ceil(max_prompt_len / chunk) verifier passes of
+ * `chunk` rows per sequence, which write the prompt's K and V, and out_next_tokens[s] receives the
+ * verifier's token after the last prompt token - the first consistent token T_0 of the decoding
+ * loop, whose own K and V are not cached yet.  seq_lens is not modified; the consistent length after
+ * the call is seq_lens[s] + the prompt's length.  A sequence with an empty prompt takes no part and
+ * gets -1.  max_prompt_len (host) must be at least the longest prompt; max_context bounds
+ * seq_lens[s] + prompt length.  seq_status (or NULL) receives the OR of the passes' status bits, a
+ * prompt longer than max_prompt_len counting as LLM42_SEQ_BAD_LENGTH; a flagged sequence gets -1 and
+ * its cache slots hold nothing usable.  sampling: NULL for the greedy sampler.
+ * Workspace: llm42_prefill_workspace_bytes(model, num_seqs, chunk, max_context) bytes, 256-byte aligned.
+ * Enqueues on hip_stream and returns; allocates nothing; reads no device memory on the host. */
+llm42_status llm42_prefill_workspace_bytes(const llm42_model* model, int32_t max_seqs, int32_t chunk,
+                                           int32_t max_context, size_t* out_bytes);
+llm42_status llm42_prefill(
+    const llm42_model*    model,
+    const llm42_kv_cache* kv_cache,        /* the prompt's slots are written                */
+    const int32_t*        seq_lens,        /* dev [num_seqs]: positions already cached      */
+    const int32_t*        prompt_tokens,   /* dev: all prompts, one after the other         */
+    const int32_t*        prompt_offsets,  /* dev [num_seqs + 1], ascending                 */
+    int32_t               num_seqs,
+    int32_t               max_prompt_len,  /* host: >= every prompt's length                */
+    int32_t               chunk,           /* rows per sequence and pass, 1 .. LLM42_MAX_WINDOW */
+    int32_t               max_context,
+    int32_t*              out_next_tokens, /* dev [num_seqs]                                */
+    int32_t*              seq_status,      /* dev [num_seqs] or NULL                        */
+    void* workspace, size_t workspace_bytes, void* hip_stream,
+    const llm42_sampling* sampling);       /* or NULL                                       */
+
 /* Measurement aid (not part of the protocol; process-wide state, not thread safe).
  * While enabled, every kernel launch of class `kind` (LLM42_K_*, or -1 for all
  * classes) made by the two hot calls is bracketed by HIP events recorded on the

@@ -25,7 +25,7 @@ LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
            "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
            "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained", "llm42_decode_step", "llm42_verify_window_sampled",
-           "llm42_decode_step_sampled")
+           "llm42_decode_step_sampled", "llm42_prefill", "llm42_prefill_workspace_bytes")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
                   "argmax", "commit")
 
@@ -93,6 +93,11 @@ def load_library(path: Optional[str] = None):
     lib.llm42_decode_step.restype = i32
     lib.llm42_decode_step_sampled.argtypes = lib.llm42_decode_step.argtypes + [ctypes.POINTER(Sampling)]
     lib.llm42_decode_step_sampled.restype = i32
+    lib.llm42_prefill_workspace_bytes.argtypes = lib.llm42_workspace_bytes.argtypes
+    lib.llm42_prefill_workspace_bytes.restype = i32
+    lib.llm42_prefill.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, ctypes.c_size_t,
+                                  vp, ctypes.POINTER(Sampling)]
+    lib.llm42_prefill.restype = i32
     lib.llm42_commit_rollback.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.llm42_commit_rollback.restype = i32
     lib.llm42_profile_enable.argtypes = [i32, i32]
@@ -215,6 +220,29 @@ def llm42_decode_step(model: int, kv_base: torch.Tensor, num_blocks: int, block_
         _check(load_library().llm42_decode_step(*args))
     else:
         _check(load_library().llm42_decode_step_sampled(*args, ctypes.byref(sampling)))
+
+
+def llm42_prefill_workspace_bytes(model: int, max_seqs: int, chunk: int, max_context: int) -> int:
+    out = ctypes.c_size_t()
+    _check(load_library().llm42_prefill_workspace_bytes(model, max_seqs, chunk, max_context, ctypes.byref(out)))
+    return out.value
+
+
+def llm42_prefill(model: int, kv_base: torch.Tensor, num_blocks: int, block_table: torch.Tensor,
+                  seq_lens: torch.Tensor, prompt_tokens: torch.Tensor, prompt_offsets: torch.Tensor,
+                  max_prompt_len: int, chunk: int, max_context: int, out_next_tokens: torch.Tensor,
+                  workspace: torch.Tensor, seq_status: Optional[torch.Tensor] = None, stream=None,
+                  sampling: Optional[Sampling] = None) -> None:
+    num_seqs = seq_lens.numel()
+    if prompt_offsets.numel() != num_seqs + 1 or out_next_tokens.numel() != num_seqs:
+        raise ValueError("prompt_offsets holds num_seqs + 1 entries, out_next_tokens one per sequence")
+    kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
+    _check(load_library().llm42_prefill(
+        model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(prompt_tokens, torch.int32),
+        _ptr(prompt_offsets, torch.int32), num_seqs, max_prompt_len, chunk, max_context,
+        _ptr(out_next_tokens, torch.int32), _ptr(seq_status, torch.int32), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream),
+        ctypes.byref(sampling) if sampling is not None else None))
 
 
 def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_valid: Optional[torch.Tensor],

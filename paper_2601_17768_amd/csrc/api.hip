@@ -116,6 +116,57 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   return ws;
 }
 
+// One pass of the verifier over num_seqs x window rows; arguments already checked.
+llm42_status run_pass(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens, const int32_t* candidates,
+                      int window, const int32_t* n_valid, int num_seqs, int max_context, int32_t* out_tokens,
+                      int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids, int n_dump,
+                      const Workspace& ws, hipStream_t st, const llm42_sampling* sampling, bool prefill_pass) {
+  const llm42_config& c = m->cfg;
+  TIMED(LLM42_K_PREPARE, launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context,
+                                        dump_seq_ids, n_dump, out_tokens, seq_status, ws, st, prefill_pass));
+  TIMED(LLM42_K_PREPARE, launch_attention_plan(m, num_seqs, ws, st));
+  TIMED(LLM42_K_EMBED, launch_embed(m, candidates, ws, st));
+  for (int l = 0; l < c.n_layers; ++l) {
+    const llm42_model::Layer& ly = m->layers[l];
+    TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, ly.attn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
+    TIMED(LLM42_K_QKV, launch_gemm_qkv(m, l, kv, window, ws, st));
+    TIMED(LLM42_K_ATTENTION, launch_attention(m, l, kv, num_seqs, window, max_context, ws, st));
+    TIMED(LLM42_K_O_PROJ, launch_gemm_residual(ly.wo, ws.attn, ws.resid, c.d_model, m->d_attn, ws, st));
+    TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, ly.ffn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
+    TIMED(LLM42_K_GATE_UP, launch_gemm_swiglu(m, l, ws, st));
+    TIMED(LLM42_K_DOWN, launch_gemm_residual(ly.wdown, ws.hidden, ws.resid, c.d_model, m->ffn_k, ws, st));
+  }
+  TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, m->final_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
+  TIMED(LLM42_K_LM_HEAD, launch_gemm_logits(m, window, out_logits, sampling, ws, st));
+  TIMED(LLM42_K_ARGMAX, launch_argmax_merge(m, num_seqs, window, out_tokens, ws, st));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LLM42_EHIP, "verifier pass: launch failed: %s", hipGetErrorString(e));
+  return LLM42_OK;
+}
+
+// Buffers of llm42_prefill behind the verifier's own workspace: the candidate rows of the current
+// pass, their count and the cached length per sequence, the pass's tokens, a status word per sequence.
+struct PrefillExtra {
+  int32_t *cand, *n_valid, *lens_now, *pass_tokens, *status;
+  size_t bytes;   // workspace size including these
+};
+PrefillExtra carve_prefill(size_t verifier_bytes, int num_seqs, int window, char* base) {
+  PrefillExtra x;
+  size_t off = align_up(verifier_bytes, 256);
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off = align_up(off + bytes, 256);
+    return (int32_t*)p;
+  };
+  x.cand = take(sizeof(int32_t) * (size_t)num_seqs * window);
+  x.n_valid = take(sizeof(int32_t) * num_seqs);
+  x.lens_now = take(sizeof(int32_t) * num_seqs);
+  x.pass_tokens = take(sizeof(int32_t) * (size_t)num_seqs * window);
+  x.status = take(sizeof(int32_t) * num_seqs);
+  x.bytes = off;
+  return x;
+}
+
 }  // namespace
 
 int g_llm42_unconstrained = 0;
@@ -292,29 +343,8 @@ llm42_status llm42_verify_window_sampled(const llm42_model* m, const llm42_kv_ca
   const Workspace ws = carve(m, num_seqs, window, max_context, (char*)workspace);
   if (ws.bytes > workspace_bytes)
     return fail(LLM42_EWORKSPACE, "verify_window: workspace %zu < %zu bytes", workspace_bytes, ws.bytes);
-
-  hipStream_t st = (hipStream_t)hip_stream;
-  const llm42_config& c = m->cfg;
-  TIMED(LLM42_K_PREPARE, launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context,
-                                        dump_seq_ids, n_dump, out_tokens, seq_status, ws, st));
-  TIMED(LLM42_K_PREPARE, launch_attention_plan(m, num_seqs, ws, st));
-  TIMED(LLM42_K_EMBED, launch_embed(m, candidates, ws, st));
-  for (int l = 0; l < c.n_layers; ++l) {
-    const llm42_model::Layer& ly = m->layers[l];
-    TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, ly.attn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
-    TIMED(LLM42_K_QKV, launch_gemm_qkv(m, l, kv, window, ws, st));
-    TIMED(LLM42_K_ATTENTION, launch_attention(m, l, kv, num_seqs, window, max_context, ws, st));
-    TIMED(LLM42_K_O_PROJ, launch_gemm_residual(ly.wo, ws.attn, ws.resid, c.d_model, m->d_attn, ws, st));
-    TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, ly.ffn_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
-    TIMED(LLM42_K_GATE_UP, launch_gemm_swiglu(m, l, ws, st));
-    TIMED(LLM42_K_DOWN, launch_gemm_residual(ly.wdown, ws.hidden, ws.resid, c.d_model, m->ffn_k, ws, st));
-  }
-  TIMED(LLM42_K_RMSNORM, launch_rmsnorm(ws.resid, m->final_norm, ws.normed, ws.m_pad, c.d_model, c.rms_eps, st));
-  TIMED(LLM42_K_LM_HEAD, launch_gemm_logits(m, window, n_dump > 0 ? out_logits : nullptr, sampling, ws, st));
-  TIMED(LLM42_K_ARGMAX, launch_argmax_merge(m, num_seqs, window, out_tokens, ws, st));
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(LLM42_EHIP, "verify_window: launch failed: %s", hipGetErrorString(e));
-  return LLM42_OK;
+  return run_pass(m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context, out_tokens, seq_status,
+                  n_dump > 0 ? out_logits : nullptr, dump_seq_ids, n_dump, ws, (hipStream_t)hip_stream, sampling, false);
 }
 
 llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
@@ -335,6 +365,53 @@ llm42_status llm42_decode_step_sampled(const llm42_model* m, const llm42_kv_cach
                                   nullptr, nullptr, 0, workspace, workspace_bytes, hip_stream, sampling);
   g_llm42_unconstrained = saved;
   return st;
+}
+
+llm42_status llm42_prefill_workspace_bytes(const llm42_model* m, int32_t max_seqs, int32_t chunk, int32_t max_context,
+                                           size_t* out_bytes) {
+  size_t v = 0;
+  if (llm42_status st = llm42_workspace_bytes(m, max_seqs, chunk, max_context, &v)) return st;
+  *out_bytes = carve_prefill(v, max_seqs, chunk, nullptr).bytes;
+  return LLM42_OK;
+}
+
+llm42_status llm42_prefill(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                           const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t num_seqs,
+                           int32_t max_prompt_len, int32_t chunk, int32_t max_context, int32_t* out_next_tokens,
+                           int32_t* seq_status, void* workspace, size_t workspace_bytes, void* hip_stream,
+                           const llm42_sampling* sampling) {
+  if (sampling && !(sampling->temperature >= 0.f)) return fail(LLM42_EINVAL, "prefill: negative temperature");
+  if (!m || !kv || !seq_lens || !prompt_tokens || !prompt_offsets || !out_next_tokens || !workspace)
+    return fail(LLM42_EINVAL, "prefill: null argument");
+  if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
+    return fail(LLM42_EINVAL, "prefill: bad kv_cache view");
+  if (chunk < 1 || chunk > LLM42_MAX_WINDOW) return fail(LLM42_EINVAL, "prefill: chunk must be 1..%d", LLM42_MAX_WINDOW);
+  if (num_seqs < 1 || (int64_t)num_seqs * chunk > (1 << 20)) return fail(LLM42_EINVAL, "prefill: bad num_seqs");
+  if (max_prompt_len < 0 || max_context < 1) return fail(LLM42_EINVAL, "prefill: bad max_prompt_len / max_context");
+  if (max_context > m->cfg.max_position)
+    return fail(LLM42_ECAPACITY, "prefill: max_context %d exceeds max_position %d", max_context, m->cfg.max_position);
+  if ((int64_t)max_context > (int64_t)kv->max_blocks_per_seq * LLM42_KV_BLOCK)
+    return fail(LLM42_ECAPACITY, "prefill: max_context %d exceeds block-table capacity %lld", max_context,
+                (long long)kv->max_blocks_per_seq * LLM42_KV_BLOCK);
+  if ((uintptr_t)workspace % 256) return fail(LLM42_EWORKSPACE, "prefill: workspace not 256-byte aligned");
+  const Workspace ws = carve(m, num_seqs, chunk, max_context, (char*)workspace);
+  const PrefillExtra x = carve_prefill(ws.bytes, num_seqs, chunk, (char*)workspace);
+  if (x.bytes > workspace_bytes) return fail(LLM42_EWORKSPACE, "prefill: workspace %zu < %zu bytes", workspace_bytes, x.bytes);
+  hipStream_t st = (hipStream_t)hip_stream;
+  int32_t* status = seq_status ? seq_status : x.status;
+  const int passes = max_prompt_len == 0 ? 1 : (max_prompt_len + chunk - 1) / chunk;   // one pass at least: it sets the outputs
+  for (int p = 0; p < passes; ++p) {
+    launch_prefill_window(prompt_tokens, prompt_offsets, seq_lens, num_seqs, chunk, p, max_prompt_len, x.cand, x.n_valid,
+                          x.lens_now, status, out_next_tokens, st);
+    if (max_prompt_len == 0) break;
+    if (llm42_status rc = run_pass(m, kv, x.lens_now, x.cand, chunk, x.n_valid, num_seqs, max_context, x.pass_tokens, status,
+                                   nullptr, nullptr, 0, ws, st, sampling, true))
+      return rc;
+    launch_prefill_pick(prompt_offsets, num_seqs, chunk, p, x.pass_tokens, status, out_next_tokens, st);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LLM42_EHIP, "prefill: launch failed: %s", hipGetErrorString(e));
+  return LLM42_OK;
 }
 
 llm42_status llm42_commit_rollback(const int32_t* candidates, const int32_t* out_tokens, const int32_t* n_valid,

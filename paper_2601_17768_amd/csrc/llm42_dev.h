@@ -118,7 +118,12 @@ void launch_pack_gate_up(const uint16_t* wg, const uint16_t* wu, uint16_t* dst, 
 void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
                     const int32_t* candidates, const int32_t* n_valid, int num_seqs, int window,
                     int max_context, const int32_t* dump_seq_ids, int n_dump, int32_t* out_tokens,
-                    int32_t* seq_status, const Workspace& ws, hipStream_t st);
+                    int32_t* seq_status, const Workspace& ws, hipStream_t st, bool prefill_pass);
+void launch_prefill_window(const int32_t* prompt_tokens, const int32_t* prompt_offsets, const int32_t* seq_lens,
+                           int num_seqs, int window, int chunk_index, int max_prompt_len, int32_t* cand,
+                           int32_t* n_valid, int32_t* lens_now, int32_t* seq_status, int32_t* out_next, hipStream_t st);
+void launch_prefill_pick(const int32_t* prompt_offsets, int num_seqs, int window, int chunk_index,
+                         const int32_t* pass_tokens, const int32_t* seq_status, int32_t* out_next, hipStream_t st);
 void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspace& ws, hipStream_t st);
 void launch_rmsnorm(const float* x, const uint16_t* gain, uint16_t* y, int m_pad, int d, float eps,
                     hipStream_t st);

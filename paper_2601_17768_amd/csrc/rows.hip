@@ -14,7 +14,7 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
                                const int32_t* __restrict__ dump_seq_ids, int n_dump, int32_t* out_tokens,
                                int32_t* seq_status, int32_t* row_pos, int32_t* row_seq, int32_t* ws_len,
                                int32_t* ws_n, int32_t* dump_slot, const float2* __restrict__ rope, int half_dim,
-                               int32_t* row_blk, float2* row_rope) {
+                               int32_t* row_blk, float2* row_rope, int min_n, int status_or) {
   __shared__ int status;
   const int s = blockIdx.x;
   if (threadIdx.x == 0) status = 0;
@@ -22,7 +22,8 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
   const int L = seq_lens[s];
   const int n = n_valid ? n_valid[s] : window;
   int bad = 0;
-  if (L < 0 || n < 1 || n > window || (int64_t)L + n > max_context) bad = LLM42_SEQ_BAD_LENGTH;
+  // (min_n is 1; a prefill pass passes 0: a sequence whose prompt has ended takes no part in the pass)
+  if (L < 0 || n < min_n || n > window || (int64_t)L + n > max_context) bad = LLM42_SEQ_BAD_LENGTH;
   if (!bad) {
     const int blocks = (L + n + LLM42_KV_BLOCK - 1) / LLM42_KV_BLOCK;   // <= max_blocks_per_seq (host checked)
     for (int b = threadIdx.x; b < blocks; b += blockDim.x) {
@@ -55,9 +56,9 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
     }
   }
   if (threadIdx.x == 0) {
-    ws_len[s] = st == 0 ? L : -1;
+    ws_len[s] = st == 0 && n > 0 ? L : -1;
     ws_n[s] = st == 0 ? n : 0;
-    if (seq_status) seq_status[s] = st;
+    if (seq_status) seq_status[s] = status_or ? (seq_status[s] | st) : st;
     int slot = -1;
     for (int j = 0; j < n_dump; ++j)
       if (dump_seq_ids[j] == s) slot = j;
@@ -73,6 +74,42 @@ __global__ void prepare_pad_rows_kernel(int32_t* row_pos, int32_t* row_seq, int3
     row_seq[r] = 0;
     row_blk[r] = 0;
   }
+}
+
+// Prefill, pass `chunk_index`: cuts the next `window` prompt tokens of every sequence into the
+// candidate rows of one verifier pass.  One workgroup per sequence.
+__global__ void prefill_window_kernel(const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ prompt_offsets,
+                                      const int32_t* __restrict__ seq_lens, int window, int chunk_index,
+                                      int max_prompt_len, int32_t* __restrict__ cand, int32_t* __restrict__ n_valid,
+                                      int32_t* __restrict__ lens_now, int32_t* __restrict__ seq_status,
+                                      int32_t* __restrict__ out_next) {
+  const int s = blockIdx.x;
+  const int off = prompt_offsets[s], len = prompt_offsets[s + 1] - off;
+  const int start = chunk_index * window;
+  const bool bad = off < 0 || len < 0 || len > max_prompt_len;
+  const int n = bad ? 0 : min(max(len - start, 0), window);
+  for (int i = threadIdx.x; i < window; i += blockDim.x) cand[(size_t)s * window + i] = i < n ? prompt_tokens[off + start + i] : 0;
+  if (threadIdx.x == 0) {
+    n_valid[s] = n;
+    lens_now[s] = seq_lens[s] + (n > 0 ? start : 0);
+    if (chunk_index == 0) {
+      if (seq_status) seq_status[s] = bad ? LLM42_SEQ_BAD_LENGTH : 0;
+      out_next[s] = -1;
+    }
+  }
+}
+
+// After a prefill pass: the sequences whose last prompt token was in this pass take the pass's
+// token for that row.  A sequence that failed a check keeps -1.
+__global__ void prefill_pick_kernel(const int32_t* __restrict__ prompt_offsets, int window, int chunk_index,
+                                    const int32_t* __restrict__ pass_tokens, int num_seqs,
+                                    const int32_t* __restrict__ seq_status, int32_t* __restrict__ out_next) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= num_seqs) return;
+  const int len = prompt_offsets[s + 1] - prompt_offsets[s];
+  const int last = len - 1 - chunk_index * window;        // row of the last prompt token in this pass
+  if (len > 0 && last >= 0 && last < window)
+    out_next[s] = seq_status[s] == 0 ? pass_tokens[(size_t)s * window + last] : -1;
 }
 
 // One wave per 16 rows x 32 features of the residual stream: lane
@@ -263,15 +300,28 @@ __global__ __launch_bounds__(1024) void rmsnorm_block_kernel(const float* __rest
 void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
                     const int32_t* candidates, const int32_t* n_valid, int num_seqs, int window,
                     int max_context, const int32_t* dump_seq_ids, int n_dump, int32_t* out_tokens,
-                    int32_t* seq_status, const Workspace& ws, hipStream_t st) {
+                    int32_t* seq_status, const Workspace& ws, hipStream_t st, bool prefill_pass) {
   prepare_kernel<<<num_seqs, 64, 0, st>>>(seq_lens, candidates, n_valid, kv->block_table, kv->max_blocks_per_seq,
                                           kv->num_blocks, window, max_context, m->cfg.vocab, dump_seq_ids, n_dump,
                                           out_tokens, seq_status, ws.row_pos, ws.row_seq, ws.seq_len, ws.seq_n,
                                           ws.dump_slot, (const float2*)m->rope, m->cfg.head_dim / 2, ws.row_blk,
-                                          ws.row_rope);
+                                          ws.row_rope, prefill_pass ? 0 : 1, prefill_pass ? 1 : 0);
   if (ws.m_pad > ws.m_rows)
     prepare_pad_rows_kernel<<<(ws.m_pad - ws.m_rows + 63) / 64, 64, 0, st>>>(ws.row_pos, ws.row_seq, ws.row_blk,
                                                                             ws.m_rows, ws.m_pad);
+}
+
+void launch_prefill_window(const int32_t* prompt_tokens, const int32_t* prompt_offsets, const int32_t* seq_lens,
+                           int num_seqs, int window, int chunk_index, int max_prompt_len, int32_t* cand,
+                           int32_t* n_valid, int32_t* lens_now, int32_t* seq_status, int32_t* out_next, hipStream_t st) {
+  prefill_window_kernel<<<num_seqs, 64, 0, st>>>(prompt_tokens, prompt_offsets, seq_lens, window, chunk_index, max_prompt_len, cand,
+                                                 n_valid, lens_now, seq_status, out_next);
+}
+
+void launch_prefill_pick(const int32_t* prompt_offsets, int num_seqs, int window, int chunk_index,
+                         const int32_t* pass_tokens, const int32_t* seq_status, int32_t* out_next, hipStream_t st) {
+  prefill_pick_kernel<<<(num_seqs + 255) / 256, 256, 0, st>>>(prompt_offsets, window, chunk_index, pass_tokens, num_seqs,
+                                                             seq_status, out_next);
 }
 
 void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspace& ws, hipStream_t st) {

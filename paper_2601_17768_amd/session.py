@@ -89,10 +89,35 @@ class VerifierSession:
         return counts, tokens, rolled
 
     def prefill(self, kv: torch.Tensor, block_table: torch.Tensor, prompts: Sequence[np.ndarray],
-                window: int = 32) -> torch.Tensor:
-        """Deterministic prefill by teacher forcing: the prompts are pushed through
-        llm42_verify_window in windows (the verifier's logits do not depend on how
-        positions are cut into windows).  Returns the first output token of each sequence."""
+                window: int = 32, cached: Optional[torch.Tensor] = None, sampling=None) -> torch.Tensor:
+        """One llm42_prefill call: the prompts are appended behind the `cached` positions (int32 [n_seq] on
+        the device; none by default) in passes of `window` rows per sequence.  Returns the first output
+        token of each sequence (device, int32).  Raises if a sequence was flagged."""
+        n_seq = len(prompts)
+        lens = np.array([len(p) for p in prompts], dtype=np.int64)
+        offsets = np.zeros(n_seq + 1, dtype=np.int32)
+        offsets[1:] = np.cumsum(lens)
+        flat = np.concatenate([np.asarray(p, dtype=np.int32) for p in prompts]) if lens.sum() else np.zeros(1, np.int32)
+        if cached is None:
+            cached = torch.zeros(n_seq, dtype=torch.int32, device=self.device)
+        max_context = min(block_table.shape[1] * B.LLM42_KV_BLOCK, self.cfg.max_position)
+        need = B.llm42_prefill_workspace_bytes(self.model, n_seq, window, max_context)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        first = torch.empty(n_seq, dtype=torch.int32, device=self.device)
+        status = torch.empty(n_seq, dtype=torch.int32, device=self.device)
+        B.llm42_prefill(self.model, kv, kv.shape[2], block_table, cached, torch.as_tensor(flat, device=self.device),
+                        torch.as_tensor(offsets, device=self.device), int(lens.max()), window, max_context, first,
+                        self._ws, status, sampling=sampling)
+        if int(status.max()) != 0:
+            raise RuntimeError(f"prefill: sequence status {status.tolist()}")
+        return first
+
+    def prefill_by_windows(self, kv: torch.Tensor, block_table: torch.Tensor, prompts: Sequence[np.ndarray],
+                           window: int = 32) -> torch.Tensor:
+        """The same prefill driven from the host through llm42_verify_window, one call per window over
+        the sequences that still have prompt tokens left (what llm42_prefill must reproduce bit for bit).
+        Returns the first output token of each sequence."""
         n_seq = len(prompts)
         lens = np.array([len(p) for p in prompts], dtype=np.int32)
         done = np.zeros(n_seq, dtype=np.int32)
