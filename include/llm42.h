@@ -52,7 +52,7 @@ typedef int32_t llm42_status;
 #define LLM42_EHIP        -5  /* a HIP call or kernel launch failed                       */
 
 #define LLM42_KV_BLOCK 16     /* tokens per KV-cache block; the only supported value      */
-#define LLM42_MAX_WINDOW 64   /* largest verification window [Table 1: 32-64 in practice] */
+#define LLM42_MAX_WINDOW 512  /* largest verification window (the window ablation of SS 5.3 spans 16 .. 512) */
 
 /* Per-sequence status bits written to `seq_status` by llm42_verify_window. */
 #define LLM42_SEQ_OK            0

@@ -72,6 +72,12 @@ def test_widest_window_ragged_rows_and_an_empty_prefix(tiny):
     _run_and_compare(tiny, lens=[0, 37, 255], window=64, n_valid=[64, 1, 33], seed=101)
 
 
+def test_windows_beyond_64_rows_per_sequence(tiny):
+    # the window ablation of the paper's section 5.3 goes up to 512 inputs per request
+    _run_and_compare(tiny, lens=[0, 37, 100], window=160, n_valid=[160, 129, 65], seed=105)
+    _run_and_compare(tiny, lens=[20], window=512, n_valid=[500], seed=106)
+
+
 def test_window_of_one_row(tiny):
     _run_and_compare(tiny, lens=[1, 63, 64, 300], window=1, n_valid=None, seed=102)
 

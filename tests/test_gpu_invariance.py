@@ -102,6 +102,42 @@ def test_split_of_positions_into_windows_does_not_matter(env):
     assert torch.isfinite(ref[0]).all()
 
 
+def test_split_into_wide_windows_does_not_matter_either(env):
+    """The same for windows beyond 64 rows (up to the largest, 512)."""
+    shape, w, sess = env
+    rng = wl.rng_for(42, 15)
+    prompt = wl.random_tokens(rng, 41, shape.vocab)
+    tokens = wl.random_tokens(rng, 300, shape.vocab)
+    table, num_blocks = wl.make_block_table(rng, [41 + 300], 16, spare_blocks=1)
+    bt = torch.as_tensor(table, device=DEV)
+    dump = torch.zeros(1, dtype=torch.int32, device=DEV)
+
+    def run(cuts, window):
+        kv = sess.kv_cache(num_blocks, fill=float("nan"))
+        sess.prefill(kv, bt, [prompt], window=32)
+        rows, at = [], 0
+        for n in cuts:
+            cand = np.zeros((1, window), dtype=np.int32)
+            cand[0, :n] = tokens[at:at + n]
+            _, status, logits = sess.verify(kv, bt, torch.tensor([41 + at], dtype=torch.int32, device=DEV),
+                                            torch.as_tensor(cand, device=DEV),
+                                            n_valid=torch.tensor([n], dtype=torch.int32, device=DEV),
+                                            dump_seq_ids=dump)
+            torch.cuda.synchronize()
+            assert int(status[0]) == 0
+            rows.append(logits[0, :n].cpu())
+            at += n
+        k, v = gpu_kv_tokens(kv, bt[0], 41 + 300, shape.head_dim)
+        return torch.cat(rows), k, v
+
+    ref = run([64, 64, 64, 64, 44], 64)
+    for cuts, window in (([300], 300), ([300], 512), ([128, 172], 256), ([200, 100], 200)):
+        got = run(cuts, window)
+        for a, b in zip(ref, got):
+            assert torch.equal(a, b), cuts
+    assert torch.isfinite(ref[0]).all()
+
+
 def test_stale_and_poisoned_slots_are_never_read(env):
     """Slots at or beyond the committed length hold fast-path leftovers; whatever bit
     patterns they contain (including NaN) the result is the same, and the window's
@@ -196,5 +232,5 @@ def test_host_side_errors(env):
                               torch.empty(512, dtype=torch.uint8, device=DEV))
     assert e.value.status == B.LLM42_EWORKSPACE
     with pytest.raises(B.Llm42Error) as e:
-        B.llm42_workspace_bytes(sess.model, 1, 65, 128)
+        B.llm42_workspace_bytes(sess.model, 1, B.LLM42_MAX_WINDOW + 1, 128)
     assert e.value.status == B.LLM42_EINVAL
