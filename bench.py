@@ -27,10 +27,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
-# HBM bytes per gate/up launch from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
-# profiles/gate_up_gemm_c2_pmc.md (counter x factor from a plain kernel of known traffic); valid for
-# the c2 workload and the kernel named in "roofline"
-PMC_TRAFFIC_BYTES = {"c2": 115744.9 * 1024 * (262144.0 / 131090.5) + 896.0 * 1024}
+# HBM-side bytes per gate/up launch from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
+# profiles/gate_up_gemm_c2_pmc.md and profiles/c5_gemm_attention_pmc.md (counter in KiB x the factor a
+# plain kernel of known traffic gives in the same run); valid for that workload and the kernel named in "roofline"
+PMC_TRAFFIC_BYTES = {"c2": 115742.5 * 1024 * (262144.0 / 131084.0) + 896.0 * 1024,
+                     "c5": 911950.5 * 1024 * (262144.0 / 131087.1) + 114688.0 * 1024}
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 WORKLOADS = {
     # name: (num_seqs, window, replacement rate, description)
@@ -210,6 +211,14 @@ def main():
     dt_eager = time.perf_counter() - t2
     launches = B.llm42_profile_collect(args.steps * shape.n_layers)
     assert args.no_check or torch.equal(out, eager_out)
+    if args.pmc_calibration:
+        # one plain kernel of known HBM traffic for scaling the FETCH_SIZE / WRITE_SIZE counters: reads 256 MiB, writes 256 MiB
+        cal_in = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        cal_out = torch.empty_like(cal_in)
+        torch.cuda.synchronize()
+        torch.add(cal_in, 1.0, out=cal_out)
+        torch.cuda.synchronize()
+        del cal_in, cal_out
     ms_per_step = dt * 1e3 / args.steps
     rows = num_seqs * window
     value = rows * args.steps / dt
@@ -234,7 +243,8 @@ def main():
         achieved = gu_flops / (gu_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "gate/up GEMM + SwiGLU: gemm_tiled_kernel<4, 8, 3, 2, false, SwigluEpi>",
                     "achieved": round(achieved, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                    "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
+                    "traffic": round(PMC_TRAFFIC_BYTES[args.workload]) if args.layers is None and args.workload in PMC_TRAFFIC_BYTES else None,
                     "flops_per_launch": gu_flops, "avg_launch_ms": round(gu_ms, 5), "launches_timed": len(launches)}
         # context, not part of the path: the vendor library's plain GEMM of the same shape and value
         # distribution on this machine (no SwiGLU), timed the same way - what this GPU sustains on real data

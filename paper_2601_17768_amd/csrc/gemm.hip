@@ -578,7 +578,9 @@ void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles,
   // super-tiles of g = sn x sm tiles (see the kernel): at least one per XCD if the launch has 32 tiles or more
   const int tiles = tiles_n * tiles_m * planes;
   const int g = tiles >= 256 ? 32 : tiles >= 128 ? 16 : tiles >= 64 ? 8 : 4;
-  const int sm = tiles_m >= 8 ? (g < 8 ? g : 8) : tiles_m >= 4 ? 4 : tiles_m >= 2 ? 2 : 1, sn = g / sm;
+  // (as square as the tiles allow: a 128 x 256 tile counts double on the token side)
+  const int sm_max = WBM > WBN ? 4 : 8;
+  const int sm = tiles_m >= sm_max ? (g < sm_max ? g : sm_max) : tiles_m >= 4 ? 4 : tiles_m >= 2 ? 2 : 1, sn = g / sm;
   const int supers = ((tiles_n + sn - 1) / sn) * ((tiles_m + sm - 1) / sm) * planes;
   const unsigned grid = 8u * (unsigned)g * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
