@@ -295,17 +295,24 @@ __global__ __launch_bounds__(256 * SPLIT) void gemm_coop_kernel(const bf16x8* __
 }
 
 // Small-batch kernel for wide outputs (at most 64 tokens): 8 waves per workgroup, every wave owns
-// its own block of 16 features and streams that block's weight tiles from HBM into registers, one
-// round (CH k-tiles) ahead of their use.  The activation tiles, which all 8 waves need, are fetched
+// its own block of 16 features and streams that block's weight tiles from HBM into registers, 16
+// k-tiles ahead of their use.  The activation tiles, which all 8 waves need, are fetched
 // once per workgroup and shared through LDS (double buffered), which cuts the L2 traffic for
-// activations by 8.  Accumulation order per output element: as stated above.
+// activations by 8.  Accumulation order per output element: as stated above.  A round is 16 k-tiles
+// for one or two token blocks and 8 for four (three register sets of weights then), so that the
+// registers hold the accumulators, the weights in flight and a few prefetched activation operands.
+// (The same kernel with 8 and 16 token blocks only ties the tiled kernel at 128 and 256 rows: a round's
+// arithmetic then outlasts neither the weight stream nor the latency of its own activation fetch.)
 // NBW (7 or 8) of the 8 waves own a feature block; with NBW = 7 the eighth wave only helps fetching
 // activations (this makes the grid of the 8B gate/up GEMM exactly one workgroup per CU).
 template <int MB, int NBW, class Epi>
 __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                           int n_blocks, int k_tiles, Epi epi) {
-  constexpr int CH = 16, NW = 8;
+  // A round is CH k-tiles; NSET register sets of weights: one in use, NSET - 1 in flight (16 KiB per
+  // wave whatever the round length).  The round's activation tiles go through LDS, double buffered.
+  constexpr int CH = MB <= 2 ? 16 : MB <= 8 ? 8 : 4, NSET = 16 / CH + 1, NW = 8;
   constexpr int XT = MB * CH / NW;                   // activation tiles each wave fetches per round
+  static_assert(MB * CH % NW == 0, "a round's activation tiles are dealt evenly to the waves");
   __shared__ bf16x8 xlds[2][MB * CH * 64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const bool owner = wave < NBW && blockIdx.x * NBW + wave < n_blocks;   // other waves only fetch activations
@@ -315,7 +322,7 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   f32x4 acc[MB];
 #pragma unroll
   for (int b = 0; b < MB; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  bf16x8 wa[CH], wb[CH], xg[XT];
+  bf16x8 wr[NSET][CH], xg[XT];
   const int rounds = k_tiles / CH;                   // full rounds; the rest is the tail
 
   // none of these loads sits behind a per-load condition (the compiler would serialise them)
@@ -334,41 +341,89 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
 #pragma unroll
     for (int i = 0; i < XT; ++i) xlds[buf][(i * NW + wave) * 64 + lane] = xg[i];
   };
-  auto compute = [&](const bf16x8(&cur)[CH], int buf) {
+  auto compute = [&](const bf16x8(&cur)[CH], int buf) __attribute__((always_inline)) {
+    if constexpr (MB <= 2) {
 #pragma unroll
-    for (int j = 0; j < CH; ++j)
+      for (int j = 0; j < CH; ++j)
 #pragma unroll
-      for (int b = 0; b < MB; ++b) acc[b] = mfma16(cur[j], xlds[buf][(b * CH + j) * 64 + lane], acc[b]);
+        for (int b = 0; b < MB; ++b) acc[b] = mfma16(cur[j], xlds[buf][(b * CH + j) * 64 + lane], acc[b]);
+    } else {
+      // many token blocks: the activation operands are requested from LDS PD MFMAs ahead, by hand
+      // (with the registers this full, the compiler reads each operand right before its MFMA)
+      constexpr int PD = 6, N = CH * MB;
+      bf16x8 xq[PD + 1];
+      auto operand = [&](int idx) { return xlds[buf][((idx % MB) * CH + idx / MB) * 64 + lane]; };
+#pragma unroll
+      for (int t = 0; t < PD; ++t) xq[t] = operand(t);
+#pragma unroll
+      for (int idx = 0; idx < N; ++idx) {
+        if (idx + PD < N) xq[(idx + PD) % (PD + 1)] = operand(idx + PD);
+        __builtin_amdgcn_sched_barrier(0);
+        acc[idx % MB] = mfma16(cur[idx / MB], xq[idx % (PD + 1)], acc[idx % MB]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   };
 
-  if (rounds > 0) {
-    if (owner) load_w(wa, 0);
-    load_x(0);
-  }
-  typename Epi::Pre pre[MB];
-  if (owner) {
+  // what the epilogue needs from memory: requested now (hidden behind the weight stream) while the
+  // registers allow it, at the end with 4 token blocks and more
+  constexpr bool kEarlyPre = MB < 4;
+  typename Epi::Pre pre[kEarlyPre ? MB : 1];
+  if (kEarlyPre && owner) {
 #pragma unroll
     for (int b = 0; b < MB; ++b) pre[b] = epi.pre(nb, lane, b * 16 + (lane & 15), epi.row_info(b * 16 + (lane & 15)));
   }
-  if (rounds > 0) store_x(0);
-  __syncthreads();
-  for (int r = 0; r < rounds; r += 2) {
-    // even round: consume wa / buffer 0 while wb / buffer 1 are in flight
-    if (r + 1 < rounds) {
-      if (owner) load_w(wb, r + 1);
-      load_x(r + 1);
+  // A round's body is free of branches: past the last round the loads re-read the last round (into
+  // registers and a buffer that nothing uses any more).  The activation loads of a round are issued
+  // BEFORE its weight loads: loads return in order, so the wait for the activations (they go to LDS
+  // within the round) then leaves the weight loads, which are needed NSET - 1 rounds later, in flight.
+  // Rounds come in groups of NSET without an exit in between (with one, the compiler moves a round's
+  // weight loads down to the round that uses them, which serialises fetch and arithmetic); the last
+  // rounds % NSET rounds follow as straight code.
+  auto run = [&](auto own) __attribute__((always_inline)) {
+    constexpr bool OWN = decltype(own)::value;
+    const int last = rounds - 1;
+    load_x(0);
+    if (OWN) {
+#pragma unroll
+      for (int u = 0; u < NSET - 1; ++u) load_w(wr[u], min(u, last));
     }
-    if (owner) compute(wa, 0);
-    if (r + 1 < rounds) store_x(1);
+    store_x(0);
     __syncthreads();
-    if (r + 1 >= rounds) break;
-    if (r + 2 < rounds) {
-      if (owner) load_w(wa, r + 2);
-      load_x(r + 2);
+    int flip = 0;                                    // activation buffer of the current round (NSET odd)
+    auto body = [&](auto uc, int rr) __attribute__((always_inline)) {
+      constexpr int u = decltype(uc)::value;
+      const int buf = NSET % 2 == 0 ? (u & 1) : flip;
+      load_x(min(rr + 1, last));
+      // the set that the previous round used up takes the round NSET - 1 ahead
+      if (OWN) load_w(wr[(u + NSET - 1) % NSET], min(rr + NSET - 1, last));
+      __builtin_amdgcn_sched_barrier(0);             // (left alone the compiler sinks the loads behind the round's MFMAs)
+      if (OWN) compute(wr[u], buf);
+      store_x(buf ^ 1);
+      __syncthreads();
+      flip ^= 1;
+    };
+    int r = 0;
+    for (; r + NSET <= rounds; r += NSET) {
+      body(std::integral_constant<int, 0>{}, r);
+      body(std::integral_constant<int, 1>{}, r + 1);
+      if constexpr (NSET > 2) body(std::integral_constant<int, 2>{}, r + 2);
+      if constexpr (NSET > 3) body(std::integral_constant<int, 3>{}, r + 3);
+      if constexpr (NSET > 4) body(std::integral_constant<int, 4>{}, r + 4);
     }
-    if (owner) compute(wb, 1);
-    if (r + 2 < rounds) store_x(0);
-    __syncthreads();
+    if (r < rounds) body(std::integral_constant<int, 0>{}, r);
+    if (r + 1 < rounds) body(std::integral_constant<int, 1>{}, r + 1);
+    if constexpr (NSET > 3) {
+      if (r + 2 < rounds) body(std::integral_constant<int, 2>{}, r + 2);
+    }
+    if constexpr (NSET > 4) {
+      if (r + 3 < rounds) body(std::integral_constant<int, 3>{}, r + 3);
+    }
+  };
+  static_assert(NSET >= 2 && NSET <= 5, "the groups of rounds are written out for 2 .. 5 register sets");
+  if (rounds > 0) {
+    if (owner) run(std::true_type{});
+    else run(std::false_type{});
   }
   for (int kt = rounds * CH; owner && kt < k_tiles; ++kt) {   // tail of fewer than CH tiles: tile by tile
     const bf16x8 a = wp[(size_t)kt * 64];
@@ -377,7 +432,11 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   }
   if (owner) {
 #pragma unroll
-    for (int b = 0; b < MB; ++b) epi(nb, lane, b * 16 + (lane & 15), acc[b], pre[b]);
+    for (int b = 0; b < MB; ++b) {
+      const int row = b * 16 + (lane & 15);
+      if constexpr (kEarlyPre) epi(nb, lane, row, acc[b], pre[b]);
+      else epi(nb, lane, row, acc[b], epi.pre(nb, lane, row, epi.row_info(row)));
+    }
   }
 }
 
