@@ -14,6 +14,8 @@
 
 namespace {
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 struct QkvEpi {
   const float4* __restrict__ row_rope;    // [row][head_dim/4]: (cos, sin) of two consecutive rotary pairs at the row's position
   const int32_t* __restrict__ row_pos;
@@ -184,13 +186,20 @@ struct LogitsEpi {
 #pragma unroll
     for (int e = 1; e < 4; ++e)
       if (val[e] > bv) { bv = val[e]; bi = n0 + e; }
-    // ... then of the 4 lanes that hold the token's other features of this block
-#pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-      const float ov = __shfl_xor(bv, off);
-      const int oi = __shfl_xor(bi, off);
-      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-    }
+    // ... then of the 4 lanes that hold the token's other features of this block (lanes l ^ 16, l ^ 32).
+    // A lane swap leaves a lane's own pair and its partner's in the two results; the rule below is
+    // symmetric in the two, so every lane ends up with the same winner as with a shuffle.
+    auto better_of = [](u32x2 v, u32x2 i, float& ov, int& oi) {
+      const float v0 = __uint_as_float(v.x), v1 = __uint_as_float(v.y);
+      const int i0 = (int)i.x, i1 = (int)i.y;
+      const bool second = v1 > v0 || (v1 == v0 && i1 < i0);
+      ov = second ? v1 : v0;
+      oi = second ? i1 : i0;
+    };
+    better_of(__builtin_amdgcn_permlane16_swap(__float_as_uint(bv), __float_as_uint(bv), false, false),
+              __builtin_amdgcn_permlane16_swap((uint32_t)bi, (uint32_t)bi, false, false), bv, bi);
+    better_of(__builtin_amdgcn_permlane32_swap(__float_as_uint(bv), __float_as_uint(bv), false, false),
+              __builtin_amdgcn_permlane32_swap((uint32_t)bi, (uint32_t)bi, false, false), bv, bi);
     if (lane < 16) amax[(size_t)row * n_blocks + nb] = make_float2(bv, __int_as_float(bi));
   }
 };
