@@ -1,7 +1,7 @@
 """Full 8B shape (32 layers, d 4096, 32 q / 8 kv heads of 128, FFN 14336, vocab
 128256, random-init): parity with the stored float64 checker results of the
 single-sequence configuration, the batch-invariance stress, and the grouped
-32-sequence configuration checked through properties that hold at any size."""
+32-sequence and 128-sequence configurations checked through properties that hold at any size."""
 import json
 import os
 
@@ -15,7 +15,7 @@ from gpu_helpers import VerifierSession, gpu_kv_tokens, assert_logits_within_noi
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "c2_llama8b_window32.json")
-MAX_POS = 4352
+MAX_POS = 8320
 
 
 @pytest.fixture(scope="module")
@@ -179,3 +179,48 @@ def test_c3_grouped_sequences_properties(big):
                                    max_context=int(ctx[s]) + window)
         torch.cuda.synchronize()
         assert torch.equal(lg1[0], logits[j]) and torch.equal(o1[0], out[s])
+
+
+@pytest.mark.timeout(900)
+def test_c5_many_long_sequences_properties(big):
+    """128 sequences with contexts uniform in [1024, 8192], window 32 (4096 rows per pass, about 75 GB of
+    KV: the configuration the large-batch bench line times).  Properties instead of the checker: the
+    commit rule is exact on the library's own tokens, and sampled sequences verified alone give
+    bitwise the same logits, tokens and written K/V as inside the batch."""
+    shape, sess = big
+    window, n_seq = 32, 128
+    rng = wl.rng_for(42, 5)
+    ctx = wl.uniform_lengths(rng, n_seq, 1024, 8192)
+    table, num_blocks = wl.make_block_table(rng, ctx + window, 16, spare_blocks=8)
+    bt = torch.as_tensor(table, device=DEV)
+    kv = sess.kv_cache(num_blocks)
+    kv.normal_(generator=torch.Generator(device=DEV).manual_seed(5))
+    seq_lens = torch.as_tensor(ctx, device=DEV)
+    cand = torch.as_tensor(wl.random_tokens(rng, n_seq * window, shape.vocab).reshape(n_seq, window).astype(np.int32),
+                           device=DEV)
+    max_context = int(ctx.max()) + window
+    # one pass makes the candidates after the first input the verifier's own where they can be: some windows then match for a while
+    out, status, _ = sess.verify(kv, bt, seq_lens, cand, max_context=max_context)
+    cand[:, 1:4] = out[:, 0:3]
+    sample = [0, 57, 127]
+    dump = torch.tensor(sample, dtype=torch.int32, device=DEV)
+    out, status, logits = sess.verify(kv, bt, seq_lens, cand, dump_seq_ids=dump, max_context=max_context)
+    lens = seq_lens.clone()
+    counts, ctoks, rolled = sess.commit(cand, out, lens)
+    torch.cuda.synchronize()
+    assert int(status.max()) == 0 and torch.isfinite(logits).all()
+    cand_host, out_host = cand.cpu().numpy(), out.cpu().numpy()
+    for s in range(n_seq):
+        c, t, r = orc.commit_rollback(cand_host[s], out_host[s], window)
+        assert (int(counts[s]), int(rolled[s])) == (c, r) and c + r == window and int(lens[s]) == ctx[s] + c
+        assert ctoks[s, :c].tolist() == t
+    assert int(counts.max()) >= 2                         # the first candidate, at least, was reproduced somewhere
+    batch_kv = [gpu_kv_tokens(kv, bt[s], int(ctx[s]) + window, shape.head_dim) for s in sample]
+    for j, s in enumerate(sample):
+        o1, st1, lg1 = sess.verify(kv, bt[s:s + 1].contiguous(), seq_lens[s:s + 1].contiguous(), cand[s:s + 1].contiguous(),
+                                   dump_seq_ids=torch.zeros(1, dtype=torch.int32, device=DEV),
+                                   max_context=int(ctx[s]) + window)
+        torch.cuda.synchronize()
+        assert torch.equal(lg1[0], logits[j]) and torch.equal(o1[0], out[s]), s
+        k, v = gpu_kv_tokens(kv, bt[s], int(ctx[s]) + window, shape.head_dim)
+        assert torch.equal(k[:, ctx[s]:], batch_kv[j][0][:, ctx[s]:]) and torch.equal(v[:, ctx[s]:], batch_kv[j][1][:, ctx[s]:])
