@@ -157,7 +157,7 @@ __device__ inline void emit_normed(uint4* yr, int f, const f32x4 a, const f32x4 
   yr[(f >> 5) * 64 + ((f & 31) >> 3) * 16] = o;
 }
 
-// RMSNorm, one wave per row (4 rows per workgroup); fp32 residual stream in, bf16
+// RMSNorm, one wave per row (1 or 4 rows per workgroup); fp32 residual stream in, bf16
 // tile layout (the next GEMM's activation operand) out.
 // Reduction schedule per row (a function of d only): 64 partial sums p[w][g],
 // w = 0..15, g = 0..3; p[w][g] accumulates, in ascending feature order, the squares
@@ -167,7 +167,7 @@ __device__ inline void emit_normed(uint4* yr, int f, const f32x4 a, const f32x4 
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const uint16_t* __restrict__ gain,
                                                       uint16_t* __restrict__ y, int m_pad, int d, float eps) {
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (row >= m_pad) return;
   const int w = lane >> 2, g = lane & 3;
   const int col_tiles = d / 32;
@@ -332,5 +332,7 @@ void launch_embed(const llm42_model* m, const int32_t* candidates, const Workspa
 void launch_rmsnorm(const float* x, const uint16_t* gain, uint16_t* y, int m_pad, int d, float eps,
                     hipStream_t st) {
   if (d == 4096 && m_pad >= 256 && m_pad % 16 == 0) rmsnorm_block_kernel<<<m_pad / 16, 1024, 0, st>>>(x, gain, y, eps);
+  // few rows: one wave per workgroup, so that the rows' loads are spread over as many CUs as there are rows
+  else if (m_pad <= 256) rmsnorm_kernel<<<m_pad, 64, 0, st>>>(x, gain, y, m_pad, d, eps);
   else rmsnorm_kernel<<<(m_pad + 3) / 4, 256, 0, st>>>(x, gain, y, m_pad, d, eps);
 }
