@@ -301,7 +301,7 @@ void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_
                     const int32_t* candidates, const int32_t* n_valid, int num_seqs, int window,
                     int max_context, const int32_t* dump_seq_ids, int n_dump, int32_t* out_tokens,
                     int32_t* seq_status, const Workspace& ws, hipStream_t st, bool prefill_pass) {
-  prepare_kernel<<<num_seqs, 64, 0, st>>>(seq_lens, candidates, n_valid, kv->block_table, kv->max_blocks_per_seq,
+  prepare_kernel<<<num_seqs, 256, 0, st>>>(seq_lens, candidates, n_valid, kv->block_table, kv->max_blocks_per_seq,
                                           kv->num_blocks, window, max_context, m->cfg.vocab, dump_seq_ids, n_dump,
                                           out_tokens, seq_status, ws.row_pos, ws.row_seq, ws.seq_len, ws.seq_n,
                                           ws.dump_slot, (const float2*)m->rope, m->cfg.head_dim / 2, ws.row_blk,
