@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per gate/up launch from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
 # profiles/gate_up_gemm_c2_pmc.md and profiles/c5_gemm_attention_pmc.md (counter in KiB x the factor a
 # plain kernel of known traffic gives in the same run); valid for that workload and the kernel named in "roofline"
-PMC_TRAFFIC_BYTES = {"c2": 115742.5 * 1024 * (262144.0 / 131084.0) + 896.0 * 1024,
+PMC_TRAFFIC_BYTES = {"c2": 116600.1 * 1024 * (262144.0 / 131084.0) + 896.0 * 1024,
                      "c5": 911950.5 * 1024 * (262144.0 / 131087.1) + 114688.0 * 1024}
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 WORKLOADS = {

@@ -335,9 +335,12 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   const int rounds = k_tiles / CH;                   // full rounds; the rest is the tail
 
   // none of these loads sits behind a per-load condition (the compiler would serialise them)
+  // (a round past the last one re-reads the last round's first tile CH times: loads that keep the
+  // loop free of branches but fetch next to nothing from HBM)
   auto load_w = [&](bf16x8(&dst)[CH], int r) {
+    const int real = r < rounds ? 1 : 0, base = min(r, rounds - 1) * CH;
 #pragma unroll
-    for (int j = 0; j < CH; ++j) dst[j] = __builtin_nontemporal_load(wp + (size_t)(r * CH + j) * 64);
+    for (int j = 0; j < CH; ++j) dst[j] = __builtin_nontemporal_load(wp + (size_t)(base + j * real) * 64);
   };
   auto load_x = [&](int r) {   // tile q of the round: token block q / CH, k-tile r * CH + q % CH
 #pragma unroll
@@ -395,7 +398,7 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
     load_x(0);
     if (OWN) {
 #pragma unroll
-      for (int u = 0; u < NSET - 1; ++u) load_w(wr[u], min(u, last));
+      for (int u = 0; u < NSET - 1; ++u) load_w(wr[u], u);
     }
     store_x(0);
     __syncthreads();
@@ -405,7 +408,7 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
       const int buf = NSET % 2 == 0 ? (u & 1) : flip;
       load_x(min(rr + 1, last));
       // the set that the previous round used up takes the round NSET - 1 ahead
-      if (OWN) load_w(wr[(u + NSET - 1) % NSET], min(rr + NSET - 1, last));
+      if (OWN) load_w(wr[(u + NSET - 1) % NSET], rr + NSET - 1);
       __builtin_amdgcn_sched_barrier(0);             // (left alone the compiler sinks the loads behind the round's MFMAs)
       if (OWN) compute(wr[u], buf);
       store_x(buf ^ 1);
