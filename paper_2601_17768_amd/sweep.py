@@ -40,6 +40,12 @@ from .session import VerifierSession
 LOGNORMAL = {"sharegpt": ((4.91, 1.27), (4.77, 0.99)), "arxiv": ((8.77, 0.42), (5.25, 0.37))}
 
 
+def expected_committed(window: int, q: float) -> float:
+    """Mean number of tokens a window of `window` inputs commits when every candidate independently differs from
+    the verifier's token with probability q: the matching prefix plus the verifier's own token."""
+    return sum((1.0 - q) ** j for j in range(window))
+
+
 def contexts_for(kind: str, rng: np.random.Generator, n: int, room: int, max_position: int) -> np.ndarray:
     if kind.startswith("fixed:"):
         return np.full(n, int(kind.split(":")[1]), dtype=np.int32)
@@ -111,7 +117,7 @@ def main():
                 ws1 = sess.workspace(group, 1, max_context)
                 decode_ms[group] = _time_graph(lambda: B.llm42_decode_step(sess.model, kv, num_blocks, bt, lens, tok,
                                                                            max_context, nxt, ws1), args.reps)
-            expect = sum((1.0 - q) ** j for j in range(window))
+            expect = expected_committed(window, q)
             iteration_ms = (window - 1) * decode_ms[group] + pass_ms
             row = {"window": window, "group": group, "rows": window * group, "context_mean": round(float(ctx.mean()), 1),
                    "pass_ms": round(pass_ms, 4), "ms_per_row": round(pass_ms / (window * group), 5),
