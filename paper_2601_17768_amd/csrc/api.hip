@@ -86,6 +86,11 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   // attention work split: per chunk while the grid would otherwise be small, per super beyond that
   const int col_blocks = ws.r_pad / 16, cb_groups = (col_blocks + (col_blocks >= 8 ? 8 : 4) - 1) / (col_blocks >= 8 ? 8 : 4);
   ws.attn_super = (long long)num_seqs * c.n_kv_heads * cb_groups >= 512;
+  // contexts that fit one super need no merge pass: the attention kernel normalises and writes the output itself.
+  // With few workgroups this gives up the parallelism over chunks, which costs more than the merge pass
+  // (measured at context 512: a loss at 64 workgroups, a gain from 128).
+  ws.attn_direct = attention_units(true, max_context) == 1 && (long long)num_seqs * c.n_kv_heads * cb_groups >= 128;
+  ws.attn_super = ws.attn_super || ws.attn_direct;
   ws.attn_units = attention_units(ws.attn_super, max_context);
   size_t off = 0;
   auto take = [&](size_t bytes) {

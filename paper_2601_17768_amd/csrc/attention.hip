@@ -106,6 +106,22 @@ __device__ __forceinline__ float rows_sum(float x) {
   return __uint_as_float(r.x) + __uint_as_float(r.y);
 }
 
+// The output of query row r (of sequence s, kv head kvh) whose keys all lie in one unit: acc / l in
+// bf16, into the tile layout of the O-projection's activation operand - exactly what the merge pass
+// computes from a row's single partial.  The lane holds features d * 16 + g * 4 .. + 3 of the row.
+template <int HD>
+__device__ __forceinline__ void store_output(uint16_t* __restrict__ out, int d_attn, int s, int kvh, int group, int window,
+                                             int r, int g, const f32x4 (&acc)[HD / 16], float l) {
+  const int i = r % window, hq = kvh * group + r / window;
+#pragma unroll
+  for (int d = 0; d < HD / 16; ++d) {
+    uint2 o;
+    o.x = pack2_bf16(acc[d][0] / l, acc[d][1] / l);
+    o.y = pack2_bf16(acc[d][2] / l, acc[d][3] / l);
+    *(uint2*)(out + pk_off(s * window + i, hq * HD + d * 16 + g * 4, d_attn)) = o;
+  }
+}
+
 // One online-softmax step over the 64 keys [k0, k0 + 64): `lk` / `lv` are the step's four K and
 // four V tiles in LDS.  MASKED = false is the same arithmetic with the comparisons that cannot
 // fail left out: every key of the step is at or below every position of this wave's rows (and
@@ -228,7 +244,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
     const int4* __restrict__ items, const int32_t* __restrict__ item_count, int32_t* __restrict__ queue,
     int n_kv_heads, int group, int window, int r_pad, int y_blocks, int max_blocks_per_seq, int n_units,
-    float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml) {
+    float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ attn_out,
+    int d_attn) {
   constexpr int DK = HD / 32;        // MFMA k-steps over the head dimension (scores)
   constexpr int DB = HD / 16;        // 16-feature blocks of the output
   constexpr int TV4 = HD * 2;        // uint4 per KV tile (16 tokens x HD bf16)
@@ -382,6 +399,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     if (qpos[cb] < k_lo) continue;
+    if (SUPER && attn_out) {   // (one unit per sequence: no partial, no merge pass)
+      store_output<HD>(attn_out, d_attn, s, kvh, group, window, row[cb], g, sacc[cb], sl[cb]);
+      continue;
+    }
     const size_t prow = (((size_t)s * n_kv_heads + kvh) * n_units + unit) * r_pad + row[cb];
     float* pa = part_acc + prow * HD;
 #pragma unroll
@@ -423,7 +444,8 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
     const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int4* __restrict__ items, const int32_t* __restrict__ item_count,
     int n_kv_heads, int group, int window, int r_pad, int y_blocks, int max_blocks_per_seq, int n_units,
-    float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml) {
+    float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ attn_out,
+    int d_attn) {
   constexpr int NW = 8, CB = 1;
   constexpr int DK = HD / 32, DB = HD / 16, TV4 = HD * 2, TL = TV4 / 64;
   constexpr int UNIT = SUPER ? SUPER_KEYS : CHUNK;
@@ -558,7 +580,10 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
       entry_done();
     }
     // -- partial of this unit for every row that reaches into it
-    if (qpos[0] >= c.k_lo) {
+    if (SUPER && attn_out) {   // one unit per sequence: no partial, no merge pass
+      if (qpos[0] >= 0)
+        store_output<HD>(attn_out, d_attn, c.s, c.kvh, group, window, row[0], g, FOLD ? sacc[0] : acc[0], FOLD ? sl[0] : l[0]);
+    } else if (qpos[0] >= c.k_lo) {
       const size_t prow = (((size_t)c.s * n_kv_heads + c.kvh) * n_units + c.unit) * r_pad + row[0];
       float* pa = part_acc + prow * HD;
 #pragma unroll
@@ -692,7 +717,8 @@ void launch_one(const llm42_model* m, int layer, const uint16_t* kp, const uint1
   attention_kernel<HD, CB, NW, SUPER><<<grid, NW * 64, 0, st>>>(
       ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table, ws.seq_len, ws.seq_n, ws.attn_items, ws.attn_ctrl,
       ws.attn_ctrl + 1 + layer, c.n_kv_heads, m->group, window, ws.r_pad, y_blocks, kv->max_blocks_per_seq,
-      ws.attn_units, scale_log2, ws.part_acc, ws.part_ml);
+      ws.attn_units, scale_log2, ws.part_acc, ws.part_ml, SUPER && ws.attn_direct ? ws.attn : nullptr, m->d_attn);
+  if (SUPER && ws.attn_direct) return;
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
   attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
@@ -709,7 +735,9 @@ void launch_stream(const llm42_model* m, const uint16_t* kp, const uint16_t* vp,
   const unsigned grid = (unsigned)std::min<long long>(m->num_cus * (HD == 128 ? 1 : 2), max_items);
   attention_stream_kernel<HD, SUPER, FOLD><<<grid, 512, 0, st>>>(
       ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table, ws.attn_items, ws.attn_ctrl, c.n_kv_heads, m->group,
-      window, ws.r_pad, y_blocks, kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc, ws.part_ml);
+      window, ws.r_pad, y_blocks, kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc, ws.part_ml,
+      SUPER && ws.attn_direct ? ws.attn : nullptr, m->d_attn);
+  if (SUPER && ws.attn_direct) return;
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
   attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,

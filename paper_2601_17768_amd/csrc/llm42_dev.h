@@ -93,6 +93,7 @@ struct Workspace {
   int r_pad;      // query rows per (seq, kv head) padded to 16
   int attn_units; // attention partial slots per row (chunks or supers, see attention.hip)
   bool attn_super; // one workgroup per super (many sequences) instead of per chunk
+  bool attn_direct; // every sequence fits one super: the attention kernel writes the final output, no merge pass
   int32_t *row_pos, *row_seq, *seq_len, *seq_n, *dump_slot;
   int32_t* row_blk;    // physical KV block that holds the row's position (0 for dead rows)
   float2* row_rope;    // [m_pad][head_dim/2] (cos, sin) at the row's position

@@ -14,7 +14,8 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
                                const int32_t* __restrict__ dump_seq_ids, int n_dump, int32_t* out_tokens,
                                int32_t* seq_status, int32_t* row_pos, int32_t* row_seq, int32_t* ws_len,
                                int32_t* ws_n, int32_t* dump_slot, const float2* __restrict__ rope, int half_dim,
-                               int32_t* row_blk, float2* row_rope, int min_n, int status_or) {
+                               int32_t* row_blk, float2* row_rope, int min_n, int status_or,
+                               uint16_t* __restrict__ attn_zero, int d_attn) {
   __shared__ int status;
   const int s = blockIdx.x;
   if (threadIdx.x == 0) status = 0;
@@ -53,6 +54,15 @@ __global__ void prepare_kernel(const int32_t* __restrict__ seq_lens, const int32
     for (int e = threadIdx.x; e < n * half_dim; e += blockDim.x) {
       const int i = e / half_dim, j = e - i * half_dim;
       row_rope[(size_t)(s * window + i) * half_dim + j] = rope[(size_t)(L + i) * half_dim + j];
+    }
+  }
+  // Without a merge pass (attn_zero given) nothing writes the attention output of rows that take no part:
+  // give them zeros once, so that everything downstream of them stays finite.
+  if (attn_zero) {
+    const int chunks = d_attn / 8;
+    for (int e = threadIdx.x; e < window * chunks; e += blockDim.x) {
+      const int i = e / chunks, c8 = e - i * chunks;
+      if (st != 0 || i >= n) *(uint4*)(attn_zero + pk_off(s * window + i, c8 * 8, d_attn)) = make_uint4(0, 0, 0, 0);
     }
   }
   if (threadIdx.x == 0) {
@@ -305,7 +315,8 @@ void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_
                                           kv->num_blocks, window, max_context, m->cfg.vocab, dump_seq_ids, n_dump,
                                           out_tokens, seq_status, ws.row_pos, ws.row_seq, ws.seq_len, ws.seq_n,
                                           ws.dump_slot, (const float2*)m->rope, m->cfg.head_dim / 2, ws.row_blk,
-                                          ws.row_rope, prefill_pass ? 0 : 1, prefill_pass ? 1 : 0);
+                                          ws.row_rope, prefill_pass ? 0 : 1, prefill_pass ? 1 : 0,
+                                          ws.attn_direct ? ws.attn : nullptr, m->d_attn);
   if (ws.m_pad > ws.m_rows)
     prepare_pad_rows_kernel<<<(ws.m_pad - ws.m_rows + 63) / 64, 64, 0, st>>>(ws.row_pos, ws.row_seq, ws.row_blk,
                                                                             ws.m_rows, ws.m_pad);

@@ -138,6 +138,41 @@ def test_split_into_wide_windows_does_not_matter_either(env):
     assert torch.isfinite(ref[0]).all()
 
 
+def test_many_short_sequences_without_a_merge_pass(env):
+    """From 128 (sequence, kv head) pairs whose contexts fit one 2048-key unit the attention kernel writes its
+    output itself; rows and sequences that take no part get zeros once per call.  Every live sequence must give
+    bitwise what it gives alone (where the partials go through the merge pass), ragged and bad neighbours or not."""
+    shape, w, sess = env
+    rng = wl.rng_for(42, 16)
+    window, n_seq = 8, 70
+    lens = wl.uniform_lengths(rng, n_seq, 5, 300)
+    prompts = [wl.random_tokens(rng, int(n), shape.vocab) for n in lens]
+    table, num_blocks = wl.make_block_table(rng, lens + window, 16, spare_blocks=3)
+    bt = torch.as_tensor(table, device=DEV)
+    kv = sess.kv_cache(num_blocks, fill=float("nan"))
+    sess.prefill(kv, bt, prompts, window=16)
+    cand = wl.random_tokens(rng, n_seq * window, shape.vocab).reshape(n_seq, window).astype(np.int32)
+    n_valid = rng.integers(1, window + 1, size=n_seq).astype(np.int32)
+    n_valid[[0, 33, 69]] = window
+    cand[11, 2] = shape.vocab                      # a sequence that is switched off
+    n_valid[11] = window
+    sample = [0, 33, 69, 20]
+    d = lambda a: torch.as_tensor(a, device=DEV)
+    out, status, logits = sess.verify(kv, bt, d(lens), d(cand), n_valid=d(n_valid),
+                                      dump_seq_ids=torch.tensor(sample, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    want = [0] * n_seq
+    want[11] = B.LLM42_SEQ_BAD_TOKEN
+    assert status.tolist() == want and bool((out[11] == -1).all())
+    for j, s in enumerate(sample):
+        n = int(n_valid[s])
+        assert torch.isfinite(logits[j, :n]).all()
+        o1, st1, lg1 = sess.verify(kv, bt[s:s + 1].contiguous(), d(lens[s:s + 1]), d(cand[s:s + 1]), n_valid=d(n_valid[s:s + 1]),
+                                   dump_seq_ids=torch.zeros(1, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        assert torch.equal(lg1[0, :n], logits[j, :n]) and torch.equal(o1[0], out[s]), s
+
+
 def test_stale_and_poisoned_slots_are_never_read(env):
     """Slots at or beyond the committed length hold fast-path leftovers; whatever bit
     patterns they contain (including NaN) the result is the same, and the window's
