@@ -85,12 +85,14 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.r_pad = pad_to(m->group * window, 16);
   // attention work split: per chunk while the grid would otherwise be small, per super beyond that
   const int col_blocks = ws.r_pad / 16, cb_groups = (col_blocks + (col_blocks >= 8 ? 8 : 4) - 1) / (col_blocks >= 8 ? 8 : 4);
-  ws.attn_super = (long long)num_seqs * c.n_kv_heads * cb_groups >= 512;
-  // contexts that fit one super need no merge pass: the attention kernel normalises and writes the output itself.
-  // With few workgroups this gives up the parallelism over chunks, which costs more than the merge pass
-  // (measured at context 512: a loss at 64 workgroups, a gain from 128).
-  ws.attn_direct = attention_units(true, max_context) == 1 && (long long)num_seqs * c.n_kv_heads * cb_groups >= 128;
-  ws.attn_super = ws.attn_super || ws.attn_direct;
+  // One workgroup per 2048-key super (chunks folded in registers) once that gives enough workgroups - measured at
+  // 8 .. 32 sequences and contexts 512 .. 6000: from about 192 (pairs x supers) on it beats one workgroup per chunk
+  // plus the merge of 8 x as many partials.  Contexts that all fit one super need no merge pass at all (the
+  // attention kernel normalises and writes the output itself), which pays from 128 workgroups on.
+  const long long pairs = (long long)num_seqs * c.n_kv_heads * cb_groups;
+  const int supers = attention_units(true, max_context);
+  ws.attn_direct = supers == 1 && pairs >= 128;
+  ws.attn_super = ws.attn_direct || pairs * supers >= 192;
   ws.attn_units = attention_units(ws.attn_super, max_context);
   size_t off = 0;
   auto take = [&](size_t bytes) {
