@@ -136,6 +136,17 @@ def _stream_handle(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
+def _kv_view(model: int, kv_base: torch.Tensor, num_blocks: int, block_table: torch.Tensor, num_seqs: int) -> KVCache:
+    """The C struct for a KV tensor and its block table; refuses a tensor smaller than num_blocks blocks need
+    (the library sees a bare pointer and could not tell)."""
+    if block_table.dim() != 2 or block_table.shape[0] != num_seqs:
+        raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
+    need = llm42_kv_bytes(model, num_blocks)
+    if kv_base.numel() * kv_base.element_size() < need:
+        raise ValueError(f"kv_base holds {kv_base.numel() * kv_base.element_size()} bytes, {num_blocks} blocks need {need}")
+    return KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
+
+
 def make_config(shape, max_position: int) -> Config:
     """`shape` is any object with the model-dimension attributes (e.g. workloads.ModelShape)."""
     return Config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
@@ -188,12 +199,10 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
     num_seqs = seq_lens.numel()
     if candidates.shape != (num_seqs, window) or out_tokens.shape != (num_seqs, window):
         raise ValueError("candidates / out_tokens must be [num_seqs, window]")
-    if block_table.dim() != 2 or block_table.shape[0] != num_seqs:
-        raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
     n_dump = 0 if dump_seq_ids is None else dump_seq_ids.numel()
     if n_dump and (out_logits is None or out_logits.shape[0] != n_dump or out_logits.shape[1] != window):
         raise ValueError("out_logits must be [n_dump, window, vocab]")
-    kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
+    kv = _kv_view(model, kv_base, num_blocks, block_table, num_seqs)
     args = (model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(candidates, torch.int32), window,
             _ptr(n_valid, torch.int32), num_seqs, max_context, _ptr(out_tokens, torch.int32),
             _ptr(seq_status, torch.int32), _ptr(out_logits, torch.float32), _ptr(dump_seq_ids, torch.int32), n_dump,
@@ -212,7 +221,7 @@ def llm42_decode_step(model: int, kv_base: torch.Tensor, num_blocks: int, block_
     num_seqs = seq_lens.numel()
     if tokens.numel() != num_seqs or out_tokens.numel() != num_seqs:
         raise ValueError("tokens / out_tokens must hold one entry per sequence")
-    kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
+    kv = _kv_view(model, kv_base, num_blocks, block_table, num_seqs)
     args = (model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(tokens, torch.int32), num_seqs, max_context,
             _ptr(out_tokens, torch.int32), _ptr(seq_status, torch.int32), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream_handle(stream))
@@ -236,7 +245,7 @@ def llm42_prefill(model: int, kv_base: torch.Tensor, num_blocks: int, block_tabl
     num_seqs = seq_lens.numel()
     if prompt_offsets.numel() != num_seqs + 1 or out_next_tokens.numel() != num_seqs:
         raise ValueError("prompt_offsets holds num_seqs + 1 entries, out_next_tokens one per sequence")
-    kv = KVCache(_ptr(kv_base), num_blocks, _ptr(block_table, torch.int32), block_table.shape[1])
+    kv = _kv_view(model, kv_base, num_blocks, block_table, num_seqs)
     _check(load_library().llm42_prefill(
         model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(prompt_tokens, torch.int32),
         _ptr(prompt_offsets, torch.int32), num_seqs, max_prompt_len, chunk, max_context,

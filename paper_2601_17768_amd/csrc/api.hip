@@ -74,11 +74,12 @@ llm42_status check_config(const llm42_config& c) {
 }
 
 // Carve the workspace.  Called with base == nullptr to size it.
-Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context, char* base) {
+Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context, char* base, bool batch_chosen = false) {
   const llm42_config& c = m->cfg;
   Workspace ws;
   memset(&ws, 0, sizeof ws);
   ws.num_cus = m->num_cus;
+  ws.batch_chosen = batch_chosen;
   ws.m_rows = num_seqs * window;
   ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : ws.m_rows <= 64 ? 64
              : ws.m_rows <= 512 ? pad_to(ws.m_rows, 128) : pad_to(ws.m_rows, 256);
@@ -174,15 +175,46 @@ PrefillExtra carve_prefill(size_t verifier_bytes, int num_seqs, int window, char
   return x;
 }
 
-}  // namespace
+// Set by llm42_measure_unconstrained only (a process-wide measurement switch): verifier passes then run off the
+// fixed schedule.  The fast path does not go through it: llm42_decode_step passes its mode down as an argument.
+int g_measure_unconstrained = 0;
 
-int g_llm42_unconstrained = 0;
+// llm42_verify_window_sampled and llm42_decode_step_sampled behind their argument names; batch_chosen: see Workspace.
+llm42_status verify_impl(const char* who, const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                         const int32_t* candidates, int32_t window, const int32_t* n_valid, int32_t num_seqs,
+                         int32_t max_context, int32_t* out_tokens, int32_t* seq_status, float* out_logits,
+                         const int32_t* dump_seq_ids, int32_t n_dump, void* workspace, size_t workspace_bytes,
+                         void* hip_stream, const llm42_sampling* sampling, bool batch_chosen) {
+  if (sampling && !(sampling->temperature >= 0.f)) return fail(LLM42_EINVAL, "%s: negative temperature", who);
+  if (!m || !kv || !seq_lens || !candidates || !out_tokens || !workspace)
+    return fail(LLM42_EINVAL, "%s: null argument", who);
+  if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
+    return fail(LLM42_EINVAL, "%s: bad kv_cache view", who);
+  if (window < 1 || window > LLM42_MAX_WINDOW) return fail(LLM42_EINVAL, "%s: window must be 1..%d", who, LLM42_MAX_WINDOW);
+  if (num_seqs < 1 || (int64_t)num_seqs * window > (1 << 20)) return fail(LLM42_EINVAL, "%s: bad num_seqs", who);
+  if (n_dump < 0 || (n_dump > 0 && (!out_logits || !dump_seq_ids)))
+    return fail(LLM42_EINVAL, "%s: n_dump needs out_logits and dump_seq_ids", who);
+  if (max_context < 1) return fail(LLM42_EINVAL, "%s: max_context < 1", who);
+  if (max_context > m->cfg.max_position)
+    return fail(LLM42_ECAPACITY, "%s: max_context %d exceeds max_position %d", who, max_context, m->cfg.max_position);
+  if ((int64_t)max_context > (int64_t)kv->max_blocks_per_seq * LLM42_KV_BLOCK)
+    return fail(LLM42_ECAPACITY, "%s: max_context %d exceeds block-table capacity %lld", who, max_context,
+                (long long)kv->max_blocks_per_seq * LLM42_KV_BLOCK);
+  if ((uintptr_t)workspace % 256) return fail(LLM42_EWORKSPACE, "%s: workspace not 256-byte aligned", who);
+  const Workspace ws = carve(m, num_seqs, window, max_context, (char*)workspace, batch_chosen);
+  if (ws.bytes > workspace_bytes)
+    return fail(LLM42_EWORKSPACE, "%s: workspace %zu < %zu bytes", who, workspace_bytes, ws.bytes);
+  return run_pass(m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context, out_tokens, seq_status,
+                  n_dump > 0 ? out_logits : nullptr, dump_seq_ids, n_dump, ws, (hipStream_t)hip_stream, sampling, false);
+}
+
+}  // namespace
 
 extern "C" {
 
 const char* llm42_last_error(void) { return g_err; }
 
-void llm42_measure_unconstrained(int32_t on) { g_llm42_unconstrained = on ? 1 : 0; }
+void llm42_measure_unconstrained(int32_t on) { g_measure_unconstrained = on ? 1 : 0; }
 
 const char* llm42_schedule_info(void) {
   return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=2 (halves, p0+p1) for the two residual projections, 1 elsewhere; "
@@ -231,9 +263,10 @@ llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w,
   m->arena_bytes = align_up(elems * 2, 256) + rope_bytes;
   hipError_t e = hipMalloc((void**)&m->arena, m->arena_bytes);
   if (e != hipSuccess) {
+    const size_t wanted = m->arena_bytes;
     delete[] m->layers;
     delete m;
-    return fail(LLM42_EHIP, "model_create: hipMalloc(%zu): %s", m->arena_bytes, hipGetErrorString(e));
+    return fail(LLM42_EHIP, "model_create: hipMalloc(%zu): %s", wanted, hipGetErrorString(e));
   }
   uint16_t* p = m->arena;
   auto take = [&](size_t n) {
@@ -331,27 +364,9 @@ llm42_status llm42_verify_window_sampled(const llm42_model* m, const llm42_kv_ca
                                          int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids,
                                          int32_t n_dump, void* workspace, size_t workspace_bytes, void* hip_stream,
                                          const llm42_sampling* sampling) {
-  if (sampling && !(sampling->temperature >= 0.f)) return fail(LLM42_EINVAL, "verify_window: negative temperature");
-  if (!m || !kv || !seq_lens || !candidates || !out_tokens || !workspace)
-    return fail(LLM42_EINVAL, "verify_window: null argument");
-  if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
-    return fail(LLM42_EINVAL, "verify_window: bad kv_cache view");
-  if (window < 1 || window > LLM42_MAX_WINDOW) return fail(LLM42_EINVAL, "verify_window: window must be 1..%d", LLM42_MAX_WINDOW);
-  if (num_seqs < 1 || (int64_t)num_seqs * window > (1 << 20)) return fail(LLM42_EINVAL, "verify_window: bad num_seqs");
-  if (n_dump < 0 || (n_dump > 0 && (!out_logits || !dump_seq_ids)))
-    return fail(LLM42_EINVAL, "verify_window: n_dump needs out_logits and dump_seq_ids");
-  if (max_context < 1) return fail(LLM42_EINVAL, "verify_window: max_context < 1");
-  if (max_context > m->cfg.max_position)
-    return fail(LLM42_ECAPACITY, "verify_window: max_context %d exceeds max_position %d", max_context, m->cfg.max_position);
-  if ((int64_t)max_context > (int64_t)kv->max_blocks_per_seq * LLM42_KV_BLOCK)
-    return fail(LLM42_ECAPACITY, "verify_window: max_context %d exceeds block-table capacity %lld", max_context,
-                (long long)kv->max_blocks_per_seq * LLM42_KV_BLOCK);
-  if ((uintptr_t)workspace % 256) return fail(LLM42_EWORKSPACE, "verify_window: workspace not 256-byte aligned");
-  const Workspace ws = carve(m, num_seqs, window, max_context, (char*)workspace);
-  if (ws.bytes > workspace_bytes)
-    return fail(LLM42_EWORKSPACE, "verify_window: workspace %zu < %zu bytes", workspace_bytes, ws.bytes);
-  return run_pass(m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context, out_tokens, seq_status,
-                  n_dump > 0 ? out_logits : nullptr, dump_seq_ids, n_dump, ws, (hipStream_t)hip_stream, sampling, false);
+  return verify_impl("verify_window", m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context, out_tokens,
+                     seq_status, out_logits, dump_seq_ids, n_dump, workspace, workspace_bytes, hip_stream, sampling,
+                     g_measure_unconstrained != 0);
 }
 
 llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
@@ -365,18 +380,14 @@ llm42_status llm42_decode_step_sampled(const llm42_model* m, const llm42_kv_cach
                                        const int32_t* tokens, int32_t num_seqs, int32_t max_context,
                                        int32_t* out_tokens, int32_t* seq_status, void* workspace,
                                        size_t workspace_bytes, void* hip_stream, const llm42_sampling* sampling) {
-  const int saved = g_llm42_unconstrained;
-  g_llm42_unconstrained = 1;
-  const llm42_status st =
-      llm42_verify_window_sampled(m, kv, seq_lens, tokens, 1, nullptr, num_seqs, max_context, out_tokens, seq_status,
-                                  nullptr, nullptr, 0, workspace, workspace_bytes, hip_stream, sampling);
-  g_llm42_unconstrained = saved;
-  return st;
+  return verify_impl("decode_step", m, kv, seq_lens, tokens, 1, nullptr, num_seqs, max_context, out_tokens, seq_status,
+                     nullptr, nullptr, 0, workspace, workspace_bytes, hip_stream, sampling, true);
 }
 
 llm42_status llm42_prefill_workspace_bytes(const llm42_model* m, int32_t max_seqs, int32_t chunk, int32_t max_context,
                                            size_t* out_bytes) {
   size_t v = 0;
+  if (!out_bytes) return fail(LLM42_EINVAL, "prefill_workspace_bytes: null argument");
   if (llm42_status st = llm42_workspace_bytes(m, max_seqs, chunk, max_context, &v)) return st;
   *out_bytes = carve_prefill(v, max_seqs, chunk, nullptr).bytes;
   return LLM42_OK;

@@ -751,7 +751,7 @@ void launch_hd(const llm42_model* m, int layer, const uint16_t* kp, const uint16
   // that one wave's MFMAs run under the other's softmax arithmetic, as one stream per CU; fewer: 4 waves.
   const bool wide = ws.r_pad / 16 >= 8;
   if (ws.attn_super) {
-    if (wide && g_llm42_unconstrained) launch_stream<HD, true, false>(m, kp, vp, kv, num_seqs, window, ws, st);
+    if (wide && ws.batch_chosen) launch_stream<HD, true, false>(m, kp, vp, kv, num_seqs, window, ws, st);
     else if (wide) launch_stream<HD, true, true>(m, kp, vp, kv, num_seqs, window, ws, st);
     else launch_one<HD, 1, 4, true>(m, layer, kp, vp, kv, num_seqs, window, ws, st);
   } else {

@@ -760,7 +760,7 @@ void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, in
   ResidualEpi e{resid, n};
   // Off the fixed schedule (fast path, cost-of-determinism measurement) the split follows the batch,
   // as in an ordinary engine: two halves while there are few rows to spread over the device, none beyond.
-  if (g_llm42_unconstrained && ws.m_rows > 16) launch_gemm<1>(w, x, n / 16, k_padded, n, ws, false, e, st);
+  if (ws.batch_chosen && ws.m_rows > 16) launch_gemm<1>(w, x, n / 16, k_padded, n, ws, false, e, st);
   else launch_gemm<kSplit[GEMM_RESIDUAL]>(w, x, n / 16, k_padded, n, ws, false, e, st);
 }
 

@@ -94,6 +94,8 @@ struct Workspace {
   int attn_units; // attention partial slots per row (chunks or supers, see attention.hip)
   bool attn_super; // one workgroup per super (many sequences) instead of per chunk
   bool attn_direct; // every sequence fits one super: the attention kernel writes the final output, no merge pass
+  bool batch_chosen; // off the fixed schedule (fast-path decode step, cost-of-determinism measurement): the batch may
+                     // choose the split of the residual projections and the attention partials
   int32_t *row_pos, *row_seq, *seq_len, *seq_n, *dump_slot;
   int32_t* row_blk;    // physical KV block that holds the row's position (0 for dead rows)
   float2* row_rope;    // [m_pad][head_dim/2] (cos, sin) at the row's position
@@ -136,9 +138,6 @@ void launch_gemm_residual(const uint16_t* w, const uint16_t* x, float* resid, in
 void launch_gemm_swiglu(const llm42_model* m, int layer, const Workspace& ws, hipStream_t st);
 void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, const llm42_sampling* sampling,
                         const Workspace& ws, hipStream_t st);
-
-// Measurement only (llm42_measure_unconstrained): the reduction schedule may then follow the batch.
-extern int g_llm42_unconstrained;
 
 int attention_units(bool super_mode, int max_context);
 void launch_attention_plan(const llm42_model* m, int num_seqs, const Workspace& ws, hipStream_t st);
