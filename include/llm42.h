@@ -53,6 +53,7 @@ typedef int32_t llm42_status;
 
 #define LLM42_KV_BLOCK 16     /* tokens per KV-cache block; the only supported value      */
 #define LLM42_MAX_WINDOW 512  /* largest verification window (the window ablation of SS 5.3 spans 16 .. 512) */
+#define LLM42_MAX_ROWS 65536  /* most rows (num_seqs * window) of one call; beyond it the calls return LLM42_EINVAL */
 
 /* Per-sequence status bits written to `seq_status` by llm42_verify_window. */
 #define LLM42_SEQ_OK            0
@@ -149,7 +150,7 @@ llm42_status llm42_verify_window(
     const int32_t*        candidates,    /* dev [num_seqs][window]                       */
     int32_t               window,        /* 1 .. LLM42_MAX_WINDOW                        */
     const int32_t*        n_valid,       /* dev [num_seqs] or NULL (= window everywhere) */
-    int32_t               num_seqs,
+    int32_t               num_seqs,      /* >= 1, num_seqs * window <= LLM42_MAX_ROWS    */
     int32_t               max_context,
     int32_t*              out_tokens,    /* dev [num_seqs][window]                       */
     int32_t*              seq_status,    /* dev [num_seqs] or NULL                       */

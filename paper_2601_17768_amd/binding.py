@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libllm42.so")
 LLM42_OK, LLM42_EINVAL, LLM42_ESHAPE, LLM42_EWORKSPACE, LLM42_ECAPACITY, LLM42_EHIP = 0, -1, -2, -3, -4, -5
 LLM42_KV_BLOCK = 16
 LLM42_MAX_WINDOW = 512
+LLM42_MAX_ROWS = 65536
 LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0, 1, 2, 4
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",

@@ -191,7 +191,8 @@ llm42_status verify_impl(const char* who, const llm42_model* m, const llm42_kv_c
   if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
     return fail(LLM42_EINVAL, "%s: bad kv_cache view", who);
   if (window < 1 || window > LLM42_MAX_WINDOW) return fail(LLM42_EINVAL, "%s: window must be 1..%d", who, LLM42_MAX_WINDOW);
-  if (num_seqs < 1 || (int64_t)num_seqs * window > (1 << 20)) return fail(LLM42_EINVAL, "%s: bad num_seqs", who);
+  if (num_seqs < 1 || (int64_t)num_seqs * window > LLM42_MAX_ROWS)
+    return fail(LLM42_EINVAL, "%s: num_seqs * window must be 1..%d", who, LLM42_MAX_ROWS);
   if (n_dump < 0 || (n_dump > 0 && (!out_logits || !dump_seq_ids)))
     return fail(LLM42_EINVAL, "%s: n_dump needs out_logits and dump_seq_ids", who);
   if (max_context < 1) return fail(LLM42_EINVAL, "%s: max_context < 1", who);
@@ -343,7 +344,8 @@ llm42_status llm42_workspace_bytes(const llm42_model* m, int32_t max_seqs, int32
   if (!m || !out_bytes) return fail(LLM42_EINVAL, "workspace_bytes: null argument");
   if (max_seqs < 1 || window < 1 || window > LLM42_MAX_WINDOW || max_context < 1)
     return fail(LLM42_EINVAL, "workspace_bytes: max_seqs/window/max_context out of range");
-  if ((int64_t)max_seqs * window > (1 << 20)) return fail(LLM42_EINVAL, "workspace_bytes: more than 2^20 rows");
+  if ((int64_t)max_seqs * window > LLM42_MAX_ROWS)
+    return fail(LLM42_EINVAL, "workspace_bytes: more than %d rows", LLM42_MAX_ROWS);
   *out_bytes = carve(m, max_seqs, window, max_context, nullptr).bytes;
   return LLM42_OK;
 }
@@ -404,7 +406,8 @@ llm42_status llm42_prefill(const llm42_model* m, const llm42_kv_cache* kv, const
   if (!kv->kv_base || !kv->block_table || kv->num_blocks < 1 || kv->max_blocks_per_seq < 1)
     return fail(LLM42_EINVAL, "prefill: bad kv_cache view");
   if (chunk < 1 || chunk > LLM42_MAX_WINDOW) return fail(LLM42_EINVAL, "prefill: chunk must be 1..%d", LLM42_MAX_WINDOW);
-  if (num_seqs < 1 || (int64_t)num_seqs * chunk > (1 << 20)) return fail(LLM42_EINVAL, "prefill: bad num_seqs");
+  if (num_seqs < 1 || (int64_t)num_seqs * chunk > LLM42_MAX_ROWS)
+    return fail(LLM42_EINVAL, "prefill: num_seqs * chunk must be 1..%d", LLM42_MAX_ROWS);
   if (max_prompt_len < 0 || max_context < 1) return fail(LLM42_EINVAL, "prefill: bad max_prompt_len / max_context");
   if (max_context > m->cfg.max_position)
     return fail(LLM42_ECAPACITY, "prefill: max_context %d exceeds max_position %d", max_context, m->cfg.max_position);

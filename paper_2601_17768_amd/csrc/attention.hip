@@ -648,8 +648,8 @@ __global__ void attention_merge_kernel(const float* __restrict__ part_acc, const
                                        uint16_t* __restrict__ out) {
   constexpr int QUADS = HD / 4;
   const int quad = threadIdx.x % QUADS;
-  const int r = blockIdx.x * (blockDim.x / QUADS) + threadIdx.x / QUADS;
-  const int s = blockIdx.y / n_kv_heads, kvh = blockIdx.y % n_kv_heads;
+  const int r = blockIdx.y * (blockDim.x / QUADS) + threadIdx.x / QUADS;   // (pairs can outnumber what grid.y allows)
+  const int s = blockIdx.x / n_kv_heads, kvh = blockIdx.x % n_kv_heads;
   if (r >= group * window) return;
   const int L = seq_len[s], n = seq_n[s];
   const int i = r % window, hq = kvh * group + r / window;
@@ -720,7 +720,7 @@ void launch_one(const llm42_model* m, int layer, const uint16_t* kp, const uint1
       ws.attn_units, scale_log2, ws.part_acc, ws.part_ml, SUPER && ws.attn_direct ? ws.attn : nullptr, m->d_attn);
   if (SUPER && ws.attn_direct) return;
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
-  attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
+  attention_merge_kernel<HD, SUPER><<<dim3(num_seqs * c.n_kv_heads, (rows + rows_per_block - 1) / rows_per_block), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
                                                window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
 }
@@ -739,7 +739,7 @@ void launch_stream(const llm42_model* m, const uint16_t* kp, const uint16_t* vp,
       SUPER && ws.attn_direct ? ws.attn : nullptr, m->d_attn);
   if (SUPER && ws.attn_direct) return;
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
-  attention_merge_kernel<HD, SUPER><<<dim3((rows + rows_per_block - 1) / rows_per_block, num_seqs * c.n_kv_heads), 256,
+  attention_merge_kernel<HD, SUPER><<<dim3(num_seqs * c.n_kv_heads, (rows + rows_per_block - 1) / rows_per_block), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
                                                window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
 }

@@ -173,6 +173,32 @@ def test_many_short_sequences_without_a_merge_pass(env):
         assert torch.equal(lg1[0, :n], logits[j, :n]) and torch.equal(o1[0], out[s]), s
 
 
+def test_more_sequence_head_pairs_than_one_grid_axis_holds(env):
+    """40 000 sequences of one row each (the width of a decoding step, on the fixed schedule): 80 000 (sequence,
+    kv head) pairs, more than a launch can number on its second grid axis, and 40 192 padded rows through every
+    GEMM, the attention partials folded by the merge pass.  Sampled sequences must give bitwise what they give alone."""
+    shape, w, sess = env
+    rng = wl.rng_for(42, 21)
+    n_seq = 40000
+    lens = rng.integers(0, 41, size=n_seq).astype(np.int32)
+    # a table wide enough for 2080 positions: two 2048-key units per sequence, so the partials go through the merge pass
+    table, num_blocks = wl.make_block_table(rng, lens + 1, 16, max_blocks_per_seq=130, spare_blocks=2)
+    bt = torch.as_tensor(table, device=DEV)
+    kv = sess.kv_cache(num_blocks)
+    kv.normal_(generator=torch.Generator(device=DEV).manual_seed(5))
+    cand = wl.random_tokens(rng, n_seq, shape.vocab).reshape(n_seq, 1).astype(np.int32)
+    sample = [0, 1, 17, 20001, 39999]
+    d = lambda a: torch.as_tensor(a, device=DEV)
+    out, status, logits = sess.verify(kv, bt, d(lens), d(cand), dump_seq_ids=torch.tensor(sample, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    assert int(status.max()) == 0 and int(out.min()) >= 0 and torch.isfinite(logits).all()
+    for j, s in enumerate(sample):
+        o1, st1, lg1 = sess.verify(kv, bt[s:s + 1].contiguous(), d(lens[s:s + 1]), d(cand[s:s + 1]),
+                                   dump_seq_ids=torch.zeros(1, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        assert torch.equal(lg1[0], logits[j]) and torch.equal(o1[0], out[s]), s
+
+
 def test_stale_and_poisoned_slots_are_never_read(env):
     """Slots at or beyond the committed length hold fast-path leftovers; whatever bit
     patterns they contain (including NaN) the result is the same, and the window's
@@ -269,3 +295,9 @@ def test_host_side_errors(env):
     with pytest.raises(B.Llm42Error) as e:
         B.llm42_workspace_bytes(sess.model, 1, B.LLM42_MAX_WINDOW + 1, 128)
     assert e.value.status == B.LLM42_EINVAL
+    with pytest.raises(B.Llm42Error) as e:
+        B.llm42_workspace_bytes(sess.model, B.LLM42_MAX_ROWS // 2 + 1, 2, 128)      # more rows than one call takes
+    assert e.value.status == B.LLM42_EINVAL
+    with pytest.raises(ValueError):                                                  # a KV tensor too small for num_blocks
+        B.llm42_verify_window(sess.model, kv, 5, bt, d([3]), d([[1, 2, 3, 4]]), 4, None, 32,
+                              torch.empty((1, 4), dtype=torch.int32, device=DEV), sess.workspace(1, 4, 32))
