@@ -68,6 +68,7 @@ llm42_status check_config(const llm42_config& c) {
   if (c.head_dim != 64 && c.head_dim != 128) return fail(LLM42_ESHAPE, "config: head_dim must be 64 or 128");
   if (c.d_model % 128) return fail(LLM42_ESHAPE, "config: d_model must be a multiple of 128");
   if (c.d_ffn % 16 || c.vocab % 16) return fail(LLM42_ESHAPE, "config: d_ffn and vocab must be multiples of 16");
+  if (c.d_ffn < 64) return fail(LLM42_ESHAPE, "config: d_ffn must be at least 64 (each half of the split down-projection needs a k-tile)");
   if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 8)
     return fail(LLM42_ESHAPE, "config: n_q_heads must be 1..8 times n_kv_heads");
   return LLM42_OK;
