@@ -1,6 +1,7 @@
 // C ABI of the verifier library (declared in include/llm42.h): host-side
 // validation, model construction, workspace carving and the kernel sequence of
 // one verifier pass.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -91,8 +92,14 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   // 8 .. 32 sequences and contexts 512 .. 6000: from about 192 (pairs x supers) on it beats one workgroup per chunk
   // plus the merge of 8 x as many partials.  Contexts that all fit one super need no merge pass at all (the
   // attention kernel normalises and writes the output itself), which pays from 128 workgroups on.
+  // With two or more such workgroups per CU and contexts beyond one super the call may instead take whole sequences
+  // as items: one workgroup walks all supers of a (sequence, kv head), folds them in registers in the merge pass's
+  // order and writes the output (the store instructions that end a work item interrupt the workgroup's fetch stream,
+  // and a super's fp32 partial takes nine per wave where a whole sequence's bf16 rows take eight).  Whether the
+  // sequences of the call deal out evenly enough for that is decided on the device, by the plan kernel.
   const long long pairs = (long long)num_seqs * c.n_kv_heads * cb_groups;
   const int supers = attention_units(true, max_context);
+  ws.attn_seq = col_blocks >= 8 && supers > 1 && pairs >= 2LL * ws.num_cus;
   ws.attn_direct = supers == 1 && pairs >= 128;
   ws.attn_super = ws.attn_direct || pairs * supers >= 192;
   ws.attn_units = attention_units(ws.attn_super, max_context);
@@ -118,7 +125,7 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
   ws.part_ml = (float*)take(8ull * part_rows);
   ws.attn_items = (int4*)take(sizeof(int4) * (size_t)num_seqs * ws.attn_units);
-  ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (1 + c.n_layers));
+  ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (2 + c.n_layers));
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
   ws.split_part = (float*)take(ws.m_pad > 64 ? 2 * 4ull * ws.m_pad * c.d_model : 0);
   ws.bytes = off;
@@ -133,7 +140,7 @@ llm42_status run_pass(const llm42_model* m, const llm42_kv_cache* kv, const int3
   const llm42_config& c = m->cfg;
   TIMED(LLM42_K_PREPARE, launch_prepare(m, kv, seq_lens, candidates, n_valid, num_seqs, window, max_context,
                                         dump_seq_ids, n_dump, out_tokens, seq_status, ws, st, prefill_pass));
-  TIMED(LLM42_K_PREPARE, launch_attention_plan(m, num_seqs, ws, st));
+  TIMED(LLM42_K_PREPARE, launch_attention_plan(m, num_seqs, max_context, ws, st));
   TIMED(LLM42_K_EMBED, launch_embed(m, candidates, ws, st));
   for (int l = 0; l < c.n_layers; ++l) {
     const llm42_model::Layer& ly = m->layers[l];

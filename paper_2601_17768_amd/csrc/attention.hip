@@ -106,19 +106,24 @@ __device__ __forceinline__ float rows_sum(float x) {
   return __uint_as_float(r.x) + __uint_as_float(r.y);
 }
 
-// The output of query row r (of sequence s, kv head kvh) whose keys all lie in one unit: acc / l in
-// bf16, into the tile layout of the O-projection's activation operand - exactly what the merge pass
-// computes from a row's single partial.  The lane holds features d * 16 + g * 4 .. + 3 of the row.
+// The output of query row r (of sequence s, kv head kvh): acc / l in bf16, into the tile layout of the
+// O-projection's activation operand - exactly what the merge pass computes from a row's folded partials.
+// The lane holds features d * 16 + g * 4 .. + 3 of the row; the lanes g and g ^ 1 of a row trade halves so that each
+// writes 8 consecutive features of every second block d (16 bytes per lane and store, half as many stores).
+// Called by all four lanes of a row or by none.
 template <int HD>
 __device__ __forceinline__ void store_output(uint16_t* __restrict__ out, int d_attn, int s, int kvh, int group, int window,
                                              int r, int g, const f32x4 (&acc)[HD / 16], float l) {
   const int i = r % window, hq = kvh * group + r / window;
+  const bool odd = g & 1;
 #pragma unroll
-  for (int d = 0; d < HD / 16; ++d) {
-    uint2 o;
-    o.x = pack2_bf16(acc[d][0] / l, acc[d][1] / l);
-    o.y = pack2_bf16(acc[d][2] / l, acc[d][3] / l);
-    *(uint2*)(out + pk_off(s * window + i, hq * HD + d * 16 + g * 4, d_attn)) = o;
+  for (int d = 0; d < HD / 16; d += 2) {
+    const uint32_t a0 = pack2_bf16(acc[d][0] / l, acc[d][1] / l), a1 = pack2_bf16(acc[d][2] / l, acc[d][3] / l);
+    const uint32_t b0 = pack2_bf16(acc[d + 1][0] / l, acc[d + 1][1] / l), b1 = pack2_bf16(acc[d + 1][2] / l, acc[d + 1][3] / l);
+    // even g keeps block d and takes its neighbour's four features of it; odd g keeps block d + 1
+    const uint32_t t0 = __shfl_xor(odd ? a0 : b0, 16), t1 = __shfl_xor(odd ? a1 : b1, 16);
+    const u32x4 o = odd ? (u32x4){t0, t1, b0, b1} : (u32x4){a0, a1, t0, t1};
+    *(u32x4*)(out + pk_off(s * window + i, hq * HD + (d + (odd ? 1 : 0)) * 16 + (g & 2) * 4, d_attn)) = o;
   }
 }
 
@@ -439,20 +444,26 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
 // fetches is ever counted by vmcnt between the first and the last entry.  Past the last item the
 // fetch cursor issues dummy fetches into slots nothing reads, which keeps the wait count constant.
 // FOLD = false (measurement only): no chunk partials inside a super, one straight accumulation.
-template <int HD, bool SUPER, bool FOLD>
+// SEQ: an item is a whole sequence (all of its supers); the supers' partials are folded in registers, in the order
+// of the merge pass, and the kernel writes the output rows itself.  The query operands then stay in LDS instead of
+// registers (the third accumulator level needs theirs).
+template <int HD, bool SUPER, bool FOLD, bool SEQ = false>
 __global__ __launch_bounds__(512) void attention_stream_kernel(
     const uint16_t* __restrict__ q, const uint4* __restrict__ k_plane, const uint4* __restrict__ v_plane,
     const int32_t* __restrict__ block_table, const int4* __restrict__ items, const int32_t* __restrict__ item_count,
     int n_kv_heads, int group, int window, int r_pad, int y_blocks, int max_blocks_per_seq, int n_units,
     float scale_log2, float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ attn_out,
-    int d_attn) {
+    int d_attn, const int32_t* __restrict__ seq_mode) {
+  if ((*seq_mode != 0) != SEQ) return;   // the plan chose the other kind of item for this call (workgroup-uniform)
   constexpr int NW = 8, CB = 1;
   constexpr int DK = HD / 32, DB = HD / 16, TV4 = HD * 2, TL = TV4 / 64;
   constexpr int UNIT = SUPER ? SUPER_KEYS : CHUNK;
   constexpr int NBUF = 4, AHEAD = 3;
   constexpr int FI = TL;                // fetch instructions per wave per entry
   static_assert(TL % 2 == 0, "half a tile per wave");
+  static_assert(!SEQ || (SUPER && FOLD), "whole sequences are folded like supers");
   __shared__ uint4 ring[NBUF][8 * TV4];
+  __shared__ uint4 q_keep[SEQ ? 8 * TV4 : 1];   // SEQ: every wave's block of query operands for the current item
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 15, g = lane >> 4;
@@ -476,8 +487,8 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
     const int4 su = x.valid ? items[it] : make_int4(0, 0, 0, 1);
     x.s = su.x, x.unit = su.y, x.L = su.z, x.n = su.w;
     x.kvh = rem / y_blocks, x.yb = rem % y_blocks;
-    x.k_lo = x.unit * UNIT;
-    x.k_hi = min(x.L + x.n, x.k_lo + UNIT);
+    x.k_lo = SEQ ? 0 : x.unit * UNIT;
+    x.k_hi = SEQ ? x.L + x.n : min(x.L + x.n, x.k_lo + UNIT);
     x.n_steps = (x.k_hi - x.k_lo + STEP - 1) / STEP;
     return x;
   };
@@ -534,6 +545,10 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
     bf16x8 qf[CB][DK];
 #pragma unroll
     for (int d = 0; d < DK; ++d) qf[0][d] = ((const bf16x8*)ring[gidx & (NBUF - 1)])[wave * TV4 + d * 64 + lane];
+    if (SEQ) {   // (each wave keeps and re-reads its own block only: no barrier needed for it)
+#pragma unroll
+      for (int d = 0; d < DK; ++d) ((bf16x8*)q_keep)[wave * TV4 + d * 64 + lane] = qf[0][d];
+    }
     int row[CB], qpos[CB];
     row[0] = (c.yb * NW + wave) * 16 + col;
     {
@@ -546,10 +561,13 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
     wmin = __builtin_amdgcn_readfirstlane(wmin);
     float m[CB] = {-INFINITY}, l[CB] = {0.f}, sm[CB] = {-INFINITY}, sl[CB] = {0.f};
     f32x4 acc[CB][DB], sacc[CB][DB];
+    float tm = -INFINITY, tl = 0.f;   // SEQ: running fold of finished supers
+    f32x4 tacc[DB];
 #pragma unroll
     for (int d = 0; d < DB; ++d) {
       acc[0][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
       sacc[0][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      tacc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
     entry_done();
     // -- one entry per step
@@ -558,13 +576,17 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
       const int k0 = c.k_lo + j * STEP;
       const uint4* sk = &ring[gidx & (NBUF - 1)][0];
       const uint16_t* sv = (const uint16_t*)&ring[gidx & (NBUF - 1)][4 * TV4];
+      if (SEQ) {
+#pragma unroll
+        for (int d = 0; d < DK; ++d) qf[0][d] = ((const bf16x8*)q_keep)[wave * TV4 + d * 64 + lane];
+      }
       if (k0 + STEP - 1 <= wmin)                               // wave-uniform
         softmax_step<HD, CB, false>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
       else
         softmax_step<HD, CB, true>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
       if (SUPER && FOLD && ((j & 3) == 3 || j + 1 == c.n_steps)) {
         // a chunk is complete: fold it into the running super partial and start the next one afresh
-        if (j < 4) {
+        if ((SEQ ? (j & 31) : j) < 4) {
           sm[0] = m[0];
           sl[0] = l[0];
 #pragma unroll
@@ -576,11 +598,24 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
         l[0] = 0.f;
 #pragma unroll
         for (int d = 0; d < DB; ++d) acc[0][d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (SEQ && ((j & 31) == 31 || j + 1 == c.n_steps)) {
+          // a super is complete as well: the same fold one level up
+          if (j < 32) {
+            tm = sm[0];
+            tl = sl[0];
+#pragma unroll
+            for (int d = 0; d < DB; ++d) tacc[d] = sacc[0][d];
+          } else {
+            fold<DB>(tm, tl, tacc, sm[0], sl[0], sacc[0]);
+          }
+        }
       }
       entry_done();
     }
     // -- partial of this unit for every row that reaches into it
-    if (SUPER && attn_out) {   // one unit per sequence: no partial, no merge pass
+    if (SEQ) {
+      if (qpos[0] >= 0) store_output<HD>(attn_out, d_attn, c.s, c.kvh, group, window, row[0], g, tacc, tl);
+    } else if (SUPER && attn_out) {   // one unit per sequence: no partial, no merge pass
       if (qpos[0] >= 0)
         store_output<HD>(attn_out, d_attn, c.s, c.kvh, group, window, row[0], g, FOLD ? sacc[0] : acc[0], FOLD ? sl[0] : l[0]);
     } else if (qpos[0] >= c.k_lo) {
@@ -601,41 +636,86 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
 // order, which keeps the tail of a launch short); and the per-layer queue counters.  The order
 // inside a class of equal length is whatever the slot counter gives: it decides only which
 // workgroup computes an item, never a bit of the result.  One workgroup; runs once per call.
+//
+// seq_unit_keys != 0: the call may run with whole sequences as items (one unit of seq_unit_keys keys
+// per sequence) if they deal out evenly enough over seq_grid workgroups (seq_per_item workgroups per
+// item, dealt as the stream kernel deals them); the kernel lists them, adds up every workgroup's
+// entries, and keeps that list (*seq_mode = 1) if the busiest workgroup has at most 8 % more than the
+// average - else (*seq_mode = 0) it lists the units of unit_keys keys as usual.  The choice moves
+// work between kernels that compute the same bits.
 __global__ __launch_bounds__(256) void attention_plan_kernel(const int32_t* __restrict__ seq_len,
                                                              const int32_t* __restrict__ seq_n, int num_seqs,
-                                                             int unit_keys, int4* __restrict__ items,
+                                                             int unit_keys, int seq_unit_keys, int seq_per_item,
+                                                             int seq_grid, int4* __restrict__ items,
                                                              int32_t* __restrict__ item_count,
-                                                             int32_t* __restrict__ queues, int n_layers) {
-  constexpr int MAXB = SUPER_KEYS / STEP;                  // classes: steps per item, 1 .. unit_keys / 64
+                                                             int32_t* __restrict__ queues, int n_layers,
+                                                             int32_t* __restrict__ seq_mode) {
+  // classes: an item's steps in units of class_steps, 1 .. nb <= MAXB (class_steps is 1 unless a unit is a whole sequence)
+  constexpr int MAXB = SUPER_KEYS / STEP;
   __shared__ int count[MAXB + 1], cursor[MAXB + 1];
-  const int nb = unit_keys / STEP;
+  __shared__ int n_items;
+  __shared__ unsigned long long load_sum;
+  __shared__ int load_max;
   for (int l = threadIdx.x; l < n_layers; l += 256) queues[l] = 0;
-  if (threadIdx.x <= MAXB) count[threadIdx.x] = 0;
-  __syncthreads();
-  auto steps_of = [&](int keys, int u) { return (min(keys, (u + 1) * unit_keys) - u * unit_keys + STEP - 1) / STEP; };
-  for (int s = threadIdx.x; s < num_seqs; s += 256) {
-    if (seq_len[s] < 0) continue;
-    const int keys = seq_len[s] + seq_n[s];                // positions 0 .. keys-1 are attended to
-    const int full = keys / unit_keys;
-    if (full) atomicAdd(&count[nb], full);
-    if (keys % unit_keys) atomicAdd(&count[steps_of(keys, full)], 1);
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int at = 0;
-    for (int c = nb; c >= 1; --c) {                        // longest class first
-      cursor[c] = at;
-      at += count[c];
+  auto list_items = [&](const int unit, const int class_steps) {
+    const int nb = (unit / STEP + class_steps - 1) / class_steps;
+    auto class_of = [&](int keys, int u) {
+      return ((min(keys, (u + 1) * unit) - u * unit + STEP - 1) / STEP + class_steps - 1) / class_steps;
+    };
+    if (threadIdx.x <= MAXB) count[threadIdx.x] = 0;
+    __syncthreads();
+    for (int s = threadIdx.x; s < num_seqs; s += 256) {
+      if (seq_len[s] < 0) continue;
+      const int keys = seq_len[s] + seq_n[s];                // positions 0 .. keys-1 are attended to
+      const int full = keys / unit;
+      if (full) atomicAdd(&count[nb], full);
+      if (keys % unit) atomicAdd(&count[class_of(keys, full)], 1);
     }
-    *item_count = at;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int at = 0;
+      for (int c = nb; c >= 1; --c) {                        // longest class first
+        cursor[c] = at;
+        at += count[c];
+      }
+      n_items = at;
+      *item_count = at;
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < num_seqs; s += 256) {
+      if (seq_len[s] < 0) continue;
+      const int L = seq_len[s], n = seq_n[s], keys = L + n;
+      const int units = (keys + unit - 1) / unit;
+      for (int u = 0; u < units; ++u) items[atomicAdd(&cursor[class_of(keys, u)], 1)] = make_int4(s, u, L, n);
+    }
+    __syncthreads();                                         // the list is complete (and visible to this workgroup)
+  };
+  int whole = 0;
+  if (seq_unit_keys) {
+    list_items(seq_unit_keys, (seq_unit_keys / STEP + MAXB - 1) / MAXB);
+    if (threadIdx.x == 0) {
+      load_sum = 0;
+      load_max = 0;
+    }
+    __syncthreads();
+    const int total = n_items * seq_per_item;
+    for (int w = threadIdx.x; w < seq_grid; w += 256) {      // the entries workgroup w of the stream kernel would walk
+      int load = 0;
+      for (int ord = 0;; ++ord) {
+        const int t = ord * seq_grid + ((ord & 1) ? seq_grid - 1 - w : w);
+        if (t >= total) break;
+        const int4 it = items[t / seq_per_item];
+        load += (it.z + it.w + STEP - 1) / STEP + 1;
+      }
+      atomicAdd(&load_sum, (unsigned long long)load);
+      atomicMax(&load_max, load);
+    }
+    __syncthreads();
+    whole = (unsigned long long)load_max * seq_grid * 100ull <= load_sum * 108ull ? 1 : 0;
+    __syncthreads();
   }
-  __syncthreads();
-  for (int s = threadIdx.x; s < num_seqs; s += 256) {
-    if (seq_len[s] < 0) continue;
-    const int L = seq_len[s], n = seq_n[s], keys = L + n;
-    const int units = (keys + unit_keys - 1) / unit_keys;
-    for (int u = 0; u < units; ++u) items[atomicAdd(&cursor[steps_of(keys, u)], 1)] = make_int4(s, u, L, n);
-  }
+  if (!whole) list_items(unit_keys, 1);
+  if (threadIdx.x == 0) *seq_mode = whole;
 }
 
 // Fold the partials of every query row (chunks inside a super left to right, then the supers
@@ -645,7 +725,8 @@ template <int HD, bool SUPER>
 __global__ void attention_merge_kernel(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
                                        const int32_t* __restrict__ seq_len, const int32_t* __restrict__ seq_n,
                                        int n_kv_heads, int group, int window, int r_pad, int n_units, int d_attn,
-                                       uint16_t* __restrict__ out) {
+                                       uint16_t* __restrict__ out, const int32_t* __restrict__ seq_mode) {
+  if (*seq_mode) return;                // the attention kernel took whole sequences and wrote the output itself
   constexpr int QUADS = HD / 4;
   const int quad = threadIdx.x % QUADS;
   const int r = blockIdx.y * (blockDim.x / QUADS) + threadIdx.x / QUADS;   // (pairs can outnumber what grid.y allows)
@@ -722,26 +803,33 @@ void launch_one(const llm42_model* m, int layer, const uint16_t* kp, const uint1
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
   attention_merge_kernel<HD, SUPER><<<dim3(num_seqs * c.n_kv_heads, (rows + rows_per_block - 1) / rows_per_block), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
-                                               window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
+                                               window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn,
+                                               ws.attn_ctrl + 1 + c.n_layers);
 }
 
-template <int HD, bool SUPER, bool FOLD>
+// Workgroups of a stream-kernel launch: one per CU at head_dim 128 (two at 64), no more than there are items.
+long long stream_grid(const llm42_model* m, int num_seqs, int units, int r_pad) {
+  const long long max_items = (long long)num_seqs * units * m->cfg.n_kv_heads * ((r_pad / 16 + 7) / 8);
+  return std::min<long long>(m->num_cus * (m->cfg.head_dim == 128 ? 1 : 2), max_items);
+}
+
+template <int HD, bool SUPER, bool FOLD, bool SEQ = false>
 void launch_stream(const llm42_model* m, const uint16_t* kp, const uint16_t* vp, const llm42_kv_cache* kv, int num_seqs,
                    int window, const Workspace& ws, hipStream_t st) {
   const llm42_config& c = m->cfg;
   const float scale_log2 = (1.0f / sqrtf((float)c.head_dim)) * 1.44269504088896340736f;
   const int y_blocks = (ws.r_pad / 16 + 7) / 8;
-  const long long max_items = (long long)num_seqs * ws.attn_units * c.n_kv_heads * y_blocks;
-  const unsigned grid = (unsigned)std::min<long long>(m->num_cus * (HD == 128 ? 1 : 2), max_items);
-  attention_stream_kernel<HD, SUPER, FOLD><<<grid, 512, 0, st>>>(
+  const unsigned grid = (unsigned)stream_grid(m, num_seqs, SEQ ? 1 : ws.attn_units, ws.r_pad);
+  attention_stream_kernel<HD, SUPER, FOLD, SEQ><<<grid, 512, 0, st>>>(
       ws.q, (const uint4*)kp, (const uint4*)vp, kv->block_table, ws.attn_items, ws.attn_ctrl, c.n_kv_heads, m->group,
       window, ws.r_pad, y_blocks, kv->max_blocks_per_seq, ws.attn_units, scale_log2, ws.part_acc, ws.part_ml,
-      SUPER && ws.attn_direct ? ws.attn : nullptr, m->d_attn);
-  if (SUPER && ws.attn_direct) return;
+      SEQ || (SUPER && ws.attn_direct) ? ws.attn : nullptr, m->d_attn, ws.attn_ctrl + 1 + c.n_layers);
+  if (SEQ || (SUPER && ws.attn_direct)) return;
   const int rows = m->group * window, rows_per_block = 256 / (HD / 4);
   attention_merge_kernel<HD, SUPER><<<dim3(num_seqs * c.n_kv_heads, (rows + rows_per_block - 1) / rows_per_block), 256,
                                       0, st>>>(ws.part_acc, ws.part_ml, ws.seq_len, ws.seq_n, c.n_kv_heads, m->group,
-                                               window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn);
+                                               window, ws.r_pad, ws.attn_units, m->d_attn, ws.attn,
+                                               ws.attn_ctrl + 1 + c.n_layers);
 }
 
 template <int HD>
@@ -750,6 +838,9 @@ void launch_hd(const llm42_model* m, int layer, const uint16_t* kp, const uint16
   // 8 row blocks or more per (sequence, kv head): 8 waves of one row block each, two per SIMD, so
   // that one wave's MFMAs run under the other's softmax arithmetic, as one stream per CU; fewer: 4 waves.
   const bool wide = ws.r_pad / 16 >= 8;
+  // (a call that may take whole sequences as items launches that kernel too; the plan's choice, made on the device
+  // from the lengths, leaves one of the two with nothing to do)
+  if (ws.attn_seq) launch_stream<HD, true, true, true>(m, kp, vp, kv, num_seqs, window, ws, st);
   if (ws.attn_super) {
     if (wide && ws.batch_chosen) launch_stream<HD, true, false>(m, kp, vp, kv, num_seqs, window, ws, st);
     else if (wide) launch_stream<HD, true, true>(m, kp, vp, kv, num_seqs, window, ws, st);
@@ -762,9 +853,14 @@ void launch_hd(const llm42_model* m, int layer, const uint16_t* kp, const uint16
 
 }  // namespace
 
-void launch_attention_plan(const llm42_model* m, int num_seqs, const Workspace& ws, hipStream_t st) {
+void launch_attention_plan(const llm42_model* m, int num_seqs, int max_context, const Workspace& ws, hipStream_t st) {
+  // as a whole-sequence item a unit has as many keys as the longest sequence of the call may have
+  const int seq_unit_keys = ws.attn_seq ? (max_context + STEP - 1) / STEP * STEP : 0;
+  const int seq_per_item = m->cfg.n_kv_heads * ((ws.r_pad / 16 + 7) / 8);
   attention_plan_kernel<<<1, 256, 0, st>>>(ws.seq_len, ws.seq_n, num_seqs, ws.attn_super ? SUPER_KEYS : CHUNK,
-                                           ws.attn_items, ws.attn_ctrl, ws.attn_ctrl + 1, m->cfg.n_layers);
+                                           seq_unit_keys, seq_per_item, (int)stream_grid(m, num_seqs, 1, ws.r_pad),
+                                           ws.attn_items, ws.attn_ctrl, ws.attn_ctrl + 1, m->cfg.n_layers,
+                                           ws.attn_ctrl + 1 + m->cfg.n_layers);
 }
 
 int attention_units(bool super_mode, int max_context) {

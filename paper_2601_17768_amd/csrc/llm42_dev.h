@@ -94,6 +94,7 @@ struct Workspace {
   int attn_units; // attention partial slots per row (chunks or supers, see attention.hip)
   bool attn_super; // one workgroup per super (many sequences) instead of per chunk
   bool attn_direct; // every sequence fits one super: the attention kernel writes the final output, no merge pass
+  bool attn_seq;    // the call may take whole sequences as attention items (the plan kernel decides from the lengths)
   bool batch_chosen; // off the fixed schedule (fast-path decode step, cost-of-determinism measurement): the batch may
                      // choose the split of the residual projections and the attention partials
   int32_t *row_pos, *row_seq, *seq_len, *seq_n, *dump_slot;
@@ -103,7 +104,8 @@ struct Workspace {
   uint16_t *normed, *q, *attn, *hidden;
   float *part_acc, *part_ml;
   int4* attn_items;     // (sequence, unit, length, rows) of every unit that holds keys, built once per call
-  int32_t* attn_ctrl;   // [0] number of items, [1 + layer] work queue counter of that layer's attention launch
+  int32_t* attn_ctrl;   // [0] number of items, [1 + layer] work queue counter of that layer's attention launch,
+                        // [1 + n_layers] 1 if the items are whole sequences
   float* split_part;   // fp32 partials of a split GEMM on the large-batch path, [2][m_pad][d_model]
   float2* amax;   // [m_pad][vocab/16] (value, index bits)
   size_t bytes;
@@ -140,7 +142,7 @@ void launch_gemm_logits(const llm42_model* m, int window, float* out_logits, con
                         const Workspace& ws, hipStream_t st);
 
 int attention_units(bool super_mode, int max_context);
-void launch_attention_plan(const llm42_model* m, int num_seqs, const Workspace& ws, hipStream_t st);
+void launch_attention_plan(const llm42_model* m, int num_seqs, int max_context, const Workspace& ws, hipStream_t st);
 void launch_attention(const llm42_model* m, int layer, const llm42_kv_cache* kv, int num_seqs, int window,
                       int max_context, const Workspace& ws, hipStream_t st);
 void launch_argmax_merge(const llm42_model* m, int num_seqs, int window, int32_t* out_tokens, const Workspace& ws,

@@ -316,7 +316,7 @@ void launch_prepare(const llm42_model* m, const llm42_kv_cache* kv, const int32_
                                           out_tokens, seq_status, ws.row_pos, ws.row_seq, ws.seq_len, ws.seq_n,
                                           ws.dump_slot, (const float2*)m->rope, m->cfg.head_dim / 2, ws.row_blk,
                                           ws.row_rope, prefill_pass ? 0 : 1, prefill_pass ? 1 : 0,
-                                          ws.attn_direct ? ws.attn : nullptr, m->d_attn);
+                                          ws.attn_direct || ws.attn_seq ? ws.attn : nullptr, m->d_attn);
   if (ws.m_pad > ws.m_rows)
     prepare_pad_rows_kernel<<<(ws.m_pad - ws.m_rows + 63) / 64, 64, 0, st>>>(ws.row_pos, ws.row_seq, ws.row_blk,
                                                                             ws.m_rows, ws.m_pad);

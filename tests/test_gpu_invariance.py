@@ -199,6 +199,44 @@ def test_more_sequence_head_pairs_than_one_grid_axis_holds(env):
         assert torch.equal(lg1[0], logits[j]) and torch.equal(o1[0], out[s]), s
 
 
+def test_whole_sequences_as_attention_items_or_not(env):
+    """With two or more (sequence, kv head) workgroups per CU and contexts beyond one 2048-key super the plan kernel
+    may hand whole sequences to the attention workgroups (supers folded in registers, no merge pass) - if the lengths
+    of the call deal out evenly, which it decides on the device.  Two calls of 1024 sequences x 64 rows (four items
+    per workgroup): lengths that balance, and one long sequence among short ones (which falls back to per-super
+    items).  Either way sampled
+    sequences give bitwise what they give alone, where the partials go through the merge pass."""
+    shape, w, sess = env
+    window, n_seq = 64, 1024
+    d = lambda a: torch.as_tensor(a, device=DEV)
+    for case, seed in (("even", 31), ("one long", 32)):
+        rng = wl.rng_for(42, seed)
+        lens = rng.integers(2000, 2200, size=n_seq).astype(np.int32) if case == "even" else \
+            rng.integers(3, 200, size=n_seq).astype(np.int32)
+        if case == "one long":
+            lens[5] = 2150
+        table, num_blocks = wl.make_block_table(rng, lens + window, 16, max_blocks_per_seq=2304 // 16, spare_blocks=2)
+        bt = d(table)
+        kv = sess.kv_cache(num_blocks)
+        kv.normal_(generator=torch.Generator(device=DEV).manual_seed(seed))
+        cand = wl.random_tokens(rng, n_seq * window, shape.vocab).reshape(n_seq, window).astype(np.int32)
+        n_valid = rng.integers(1, window + 1, size=n_seq).astype(np.int32)
+        n_valid[[0, 5, 1023]] = window
+        sample = [0, 5, 600, 1023]
+        out, status, logits = sess.verify(kv, bt, d(lens), d(cand), n_valid=d(n_valid),
+                                          dump_seq_ids=torch.tensor(sample, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        assert int(status.max()) == 0, case
+        for j, s_ in enumerate(sample):
+            n = int(n_valid[s_])
+            assert torch.isfinite(logits[j, :n]).all(), (case, s_)
+            o1, st1, lg1 = sess.verify(kv, bt[s_:s_ + 1].contiguous(), d(lens[s_:s_ + 1]), d(cand[s_:s_ + 1]),
+                                       n_valid=d(n_valid[s_:s_ + 1]), dump_seq_ids=torch.zeros(1, dtype=torch.int32, device=DEV))
+            torch.cuda.synchronize()
+            assert torch.equal(lg1[0, :n], logits[j, :n]) and torch.equal(o1[0], out[s_]), (case, s_)
+        del kv
+
+
 def test_stale_and_poisoned_slots_are_never_read(env):
     """Slots at or beyond the committed length hold fast-path leftovers; whatever bit
     patterns they contain (including NaN) the result is the same, and the window's
