@@ -724,6 +724,15 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
   const int p = side_by_side ? 2 : 1;
   constexpr bool kLogits = std::is_same<Epi, LogitsEpi>::value, kQkv = std::is_same<Epi, QkvEpi>::value;
   const bool big = !kLogits && (kQkv ? t256 >= 2 * cus : t256 * p * 5 >= 4 * cus);
+  if constexpr (kQkv) {
+    // A 192 x 128 tile where it puts the whole QKV projection into one round of workgroups (two per CU) and the
+    // 128 x 128 tile would need a second one: 2048 rows of the 8B shape are 512 such tiles (3.67 -> 3.24 ms per pass).
+    const long long t192 = (long long)((n_blocks + 11) / 12) * (m_pad / 128);
+    if (!big && n_blocks % 12 == 0 && t192 <= 2 * cus && t128 > 2 * cus) {
+      launch_tiled<6, 4, 4, 2, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st, false);
+      return;
+    }
+  }
   if (big)
     launch_tiled<LLM42_TILE_BIG, SPLIT, Epi>(wp, xp, n_blocks, k_tiles, n, ws, epi, st, side_by_side);
   else if (t128 * p * 4 >= 3 * cus)
