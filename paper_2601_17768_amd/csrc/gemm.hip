@@ -646,13 +646,33 @@ void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles,
                   const Epi& epi, hipStream_t st, bool side_by_side = false) {
   const int tiles_n = (n_blocks + 2 * WBN - 1) / (2 * WBN), tiles_m = ws.m_pad / (32 * WBM);
   const int planes = SPLIT == 2 && side_by_side ? 2 : 1;
-  // super-tiles of g = sn x sm tiles (see the kernel): at least one per XCD if the launch has 32 tiles or more
-  const int tiles = tiles_n * tiles_m * planes;
-  const int g = tiles >= 256 ? 32 : tiles >= 128 ? 16 : tiles >= 64 ? 8 : 4;
-  // (as square as the tiles allow: a 128 x 256 tile counts double on the token side)
+  // Super-tiles of g = sn x sm tiles (see the kernel), dealt round-robin to the 8 XCDs.  sm: as square as the tiles
+  // allow (a 128 x 256 tile counts double on the token side), but the widest that leaves at most 15 % of the token
+  // columns empty - a ragged last column of super-tiles is workgroups without a tile, and those still queue for a CU
+  // with free LDS before they can leave (1280 rows took as long as 2048 that way; a column of width 1 on the other
+  // hand makes every XCD fetch 32 weight tiles per k-step, which cost 4 % at 1792 rows).  g: the largest of 32, 16, 8, 4 that leaves
+  // the busiest XCD within 3 % of the least workgroup slots any of them gives it (few super-tiles deal out unevenly).
   const int sm_max = WBM > WBN ? 4 : 8;
-  const int sm = tiles_m >= sm_max ? (g < sm_max ? g : sm_max) : tiles_m >= 4 ? 4 : tiles_m >= 2 ? 2 : 1, sn = g / sm;
-  const int supers = ((tiles_n + sn - 1) / sn) * ((tiles_m + sm - 1) / sm) * planes;
+  int g = 4, sm = 1, sn = 4, supers = 0;
+  long long least = -1;
+  for (int pass = 0; pass < 2; ++pass)
+    for (int cand = 32; cand >= 4; cand /= 2) {
+      int csm = 1;
+      for (int w = 2; w <= sm_max && w <= cand; w *= 2) {
+        const int padded = (tiles_m + w - 1) / w * w;
+        if ((padded - tiles_m) * 100 <= padded * 15) csm = w;
+      }
+      const int csn = cand / csm;
+      const int csupers = ((tiles_n + csn - 1) / csn) * ((tiles_m + csm - 1) / csm) * planes;
+      const long long per_xcd = (long long)((csupers + 7) / 8) * cand;
+      if (pass == 0) {
+        if (least < 0 || per_xcd < least) least = per_xcd;
+      } else if (per_xcd * 100 <= least * 103) {
+        g = cand, sm = csm, sn = csn, supers = csupers;
+        pass = 2;   // (the largest that qualifies: leave both loops)
+        break;
+      }
+    }
   const unsigned grid = 8u * (unsigned)g * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
     gemm_tiled_kernel<WBN, WBM, NST, WGS, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr,
