@@ -83,8 +83,10 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.num_cus = m->num_cus;
   ws.batch_chosen = batch_chosen;
   ws.m_rows = num_seqs * window;
+  // (384 padded rows would be three token tiles of 128: too few for the 128 x 128 tile to fill the device, and the
+  // 64 x 128 tile then needs a second round of workgroups - 512 padded rows run faster than 384)
   ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : ws.m_rows <= 64 ? 64
-             : ws.m_rows <= 512 ? pad_to(ws.m_rows, 128) : pad_to(ws.m_rows, 256);
+             : ws.m_rows <= 256 ? pad_to(ws.m_rows, 128) : ws.m_rows <= 512 ? 512 : pad_to(ws.m_rows, 256);
   ws.r_pad = pad_to(m->group * window, 16);
   // attention work split: per chunk while the grid would otherwise be small, per super beyond that
   const int col_blocks = ws.r_pad / 16, cb_groups = (col_blocks + (col_blocks >= 8 ? 8 : 4) - 1) / (col_blocks >= 8 ? 8 : 4);

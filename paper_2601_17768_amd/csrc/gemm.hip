@@ -730,7 +730,7 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
     }
     return;
   }
-  // More than 64 tokens: m_pad is a multiple of 128 (up to 512 rows) or of 256 (beyond).  Larger tiles
+  // More than 64 tokens: m_pad is 128, 256 or 512, or a multiple of 256 beyond that.  Larger tiles
   // move fewer operand bytes per flop, smaller ones give more workgroups; measured over 128 .. 4096 rows
   // of the 8B shapes, the best choice is the largest tile that still yields about as many workgroups as
   // the device has CUs.  Where the epilogue is heavy (rotary embedding and cache writes) the 128 x 256
