@@ -281,7 +281,7 @@ def main():
         overhead = {"fixed_schedule_ms_per_step": round(ms_per_step, 4), "batch_chosen_ms_per_step": round(free_ms, 4),
                     "overhead_frac": round(ms_per_step / free_ms - 1.0, 4),
                     "rows_with_a_different_token": int((free_out != eager_out).sum()),
-                    "what": "same kernels; residual projections unsplit above 64 rows, attention supers without chunk partials"}
+                    "what": "same kernels; residual projections unsplit above 64 rows, attention supers without chunk partials (where the work items are supers, not whole sequences)"}
     # whole-pass view: weights streamed once per step
     weight_gbs = shape.gemm_params * 2 / (ms_per_step * 1e-3) / 1e9
 

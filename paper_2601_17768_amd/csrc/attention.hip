@@ -640,7 +640,7 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
 // seq_unit_keys != 0: the call may run with whole sequences as items (one unit of seq_unit_keys keys
 // per sequence) if they deal out evenly enough over seq_grid workgroups (seq_per_item workgroups per
 // item, dealt as the stream kernel deals them); the kernel lists them, adds up every workgroup's
-// entries, and keeps that list (*seq_mode = 1) if the busiest workgroup has at most 8 % more than the
+// entries, and keeps that list (*seq_mode = 1) if the busiest workgroup has at most 5 % more than the
 // average - else (*seq_mode = 0) it lists the units of unit_keys keys as usual.  The choice moves
 // work between kernels that compute the same bits.
 __global__ __launch_bounds__(256) void attention_plan_kernel(const int32_t* __restrict__ seq_len,
@@ -711,7 +711,7 @@ __global__ __launch_bounds__(256) void attention_plan_kernel(const int32_t* __re
       atomicMax(&load_max, load);
     }
     __syncthreads();
-    whole = (unsigned long long)load_max * seq_grid * 100ull <= load_sum * 108ull ? 1 : 0;
+    whole = (unsigned long long)load_max * seq_grid * 100ull <= load_sum * 105ull ? 1 : 0;
     __syncthreads();
   }
   if (!whole) list_items(unit_keys, 1);
