@@ -38,6 +38,7 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.llm42_workspace_bytes(None, 1, 8, 64, ctypes.byref(out)) == B.LLM42_EINVAL
     assert b"null" in lib.llm42_last_error()
     assert lib.llm42_kv_bytes(None, 4, ctypes.byref(out)) == B.LLM42_EINVAL
+    assert lib.llm42_prefill_workspace_bytes(None, 1, 8, 64, None) == B.LLM42_EINVAL
     assert lib.llm42_commit_rollback(None, None, None, 1, 4, None, None, None, None, None) == B.LLM42_EINVAL
     assert lib.llm42_verify_window(None, None, None, None, 8, None, 1, 64, None, None, None, None, 0, None, 0,
                                    None) == B.LLM42_EINVAL
@@ -47,7 +48,7 @@ def test_host_side_validation_needs_no_gpu():
                 rope_theta=1e4, rms_eps=1e-5, kv_block_size=16, max_position=128)
     for bad, code in ((dict(head_dim=80), B.LLM42_ESHAPE), (dict(kv_block_size=32), B.LLM42_ESHAPE),
                       (dict(d_model=200), B.LLM42_ESHAPE), (dict(vocab=1000), B.LLM42_ESHAPE),
-                      (dict(n_kv_heads=3), B.LLM42_ESHAPE), (dict(n_layers=0), B.LLM42_EINVAL),
+                      (dict(n_kv_heads=3), B.LLM42_ESHAPE), (dict(d_ffn=48), B.LLM42_ESHAPE), (dict(n_layers=0), B.LLM42_EINVAL),
                       (dict(rope_theta=0.0), B.LLM42_EINVAL)):
         cfg = B.Config(**{**good, **bad})
         assert lib.llm42_model_create(ctypes.byref(cfg), ctypes.byref(w), ctypes.byref(handle)) == code, bad
