@@ -18,14 +18,17 @@
 // a chunk in which every key of a row is masked leaves that row's state bit for
 // bit unchanged, so rows of different positions can share a workgroup.
 //
-// Work distribution (free to change, does not touch the bits): a workgroup of 4
-// waves owns one unit of keys - a chunk (few sequences: more parallelism, chunk
-// partials are written and merge_kernel does all folds) or a whole super (many
-// sequences: chunk partials are folded in registers, 8 times fewer partials go
-// through HBM) - for up to 8 blocks of 16 query rows of one (sequence, kv head);
-// query rows are ordered r = q_head_in_group * window + i.  K and V tiles are
-// fetched once per workgroup, 128 keys at a time (the next stage's loads are issued
-// before the current stage is computed), double buffered through LDS in MFMA operand order (see the KV tile layouts in llm42.h), so no transpose is needed.
+// Work distribution (free to change, does not touch the bits): a workgroup owns one unit of the keys
+// of a (sequence, kv head) for 8 blocks of 16 query rows (attention_stream_kernel, 8 waves) or up to 4
+// (attention_kernel, 4 waves); query rows are ordered r = q_head_in_group * window + i.  A unit is
+//   a chunk          - few sequences: most parallelism; chunk partials are written and the merge
+//                      kernel does all folds;
+//   a super          - more sequences: chunks are folded in registers, 8 times fewer partials;
+//   a whole sequence - many sequences whose lengths deal out evenly (the plan kernel decides from the
+//                      lengths): supers are folded in registers too and the workgroup writes the
+//                      output rows itself, as it does whenever every context fits one super.
+// K and V tiles go from global memory straight into a ring of LDS entries of 64 keys, three entries in
+// flight, already in MFMA operand order (see the KV tile layouts in llm42.h), so nothing is transposed.
 #include <algorithm>
 #include <type_traits>
 
