@@ -4,8 +4,9 @@
 //
 // Reduction schedule (what fixes the bits of every output element): one fp32
 // accumulator per element, started at zero, updated by v_mfma_f32_16x16x32_bf16
-// over k-tiles 0, 1, 2, ... in ascending order; no split along K.  The schedule
-// depends on K only.  How many token blocks a wave owns, how many waves share a
+// over k-tiles 0, 1, 2, ... in ascending order; the two residual projections use two such
+// accumulators, one per half of K, added once at the end (kSplit below), the other GEMMs one.  The
+// schedule depends on K and on the kind of GEMM only.  How many token blocks a wave owns, how many waves share a
 // workgroup and how the grid is shaped are work-distribution choices that do not
 // touch it, so they may change with the number of rows.
 #include <type_traits>
@@ -460,9 +461,10 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
 // with conflict-free 16-byte LDS reads.  WGS workgroups share a CU: one wave per SIMD cannot keep
 // the MFMA pipe busy by itself (an MFMA loop on registers alone reaches 58 % of peak with one wave
 // per SIMD and 89 % with two), so the shipped shape is 128 x 256 with two workgroups per CU.
-// Workgroups are numbered so that the workgroups that land on one XCD (id mod 8) form a super-tile
-// of 4 x 8 tiles: weight and activation tiles are then fetched from HBM once per XCD and served
-// from that XCD's L2 to the rest of the super-tile.
+// Workgroups are numbered so that the workgroups that land on one XCD (id mod 8) form super-tiles
+// of up to 32 neighbouring tiles (shape and size chosen per launch, see launch_tiled): weight and
+// activation tiles are then fetched from HBM once per XCD and served from that XCD's L2 to the rest
+// of the super-tile.
 // Accumulation order per output element: k ascending inside [k_begin, k_begin + k_count), exactly
 // as in the small-batch kernels; with ADD_PARTIAL the other half's fp32 partial is added at the end.
 // 1 KiB from global memory (wave-uniform `base` + per-lane byte offset `voff`) straight into LDS at
