@@ -97,7 +97,7 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   // With two or more such workgroups per CU and contexts beyond one super the call may instead take whole sequences
   // as items: one workgroup walks all supers of a (sequence, kv head), folds them in registers in the merge pass's
   // order and writes the output (the store instructions that end a work item interrupt the workgroup's fetch stream,
-  // and a super's fp32 partial takes nine per wave where a whole sequence's bf16 rows take eight).  Whether the
+  // and a super's fp32 partial takes nine per wave where a whole sequence's bf16 rows take four).  Whether the
   // sequences of the call deal out evenly enough for that is decided on the device, by the plan kernel.
   const long long pairs = (long long)num_seqs * c.n_kv_heads * cb_groups;
   const int supers = attention_units(true, max_context);
