@@ -120,8 +120,8 @@ void         llm42_model_destroy(llm42_model* model);
 llm42_status llm42_kv_bytes(const llm42_model* model, int64_t num_blocks, size_t* out_bytes);
 
 /* Workspace (device scratch, 256-byte aligned) needed by llm42_verify_window for
- * up to max_seqs sequences, the given window and contexts (seq_len + n_valid) up
- * to max_context. */
+ * any call of 1 .. max_seqs sequences, the given window and contexts
+ * (seq_len + n_valid) up to max_context. */
 llm42_status llm42_workspace_bytes(const llm42_model* model, int32_t max_seqs, int32_t window,
                                    int32_t max_context, size_t* out_bytes);
 
@@ -257,31 +257,6 @@ llm42_status llm42_prefill(
     int32_t*              seq_status,      /* dev [num_seqs] or NULL                        */
     void* workspace, size_t workspace_bytes, void* hip_stream,
     const llm42_sampling* sampling);       /* or NULL                                       */
-
-/* Measurement aid (not part of the protocol; process-wide state, not thread safe).
- * While enabled, every kernel launch of class `kind` (LLM42_K_*, or -1 for all
- * classes) made by the two hot calls is bracketed by HIP events recorded on the
- * call's own stream, up to max_launches launches (further ones go untimed).
- * llm42_profile_collect waits for the recorded events, writes the duration of each
- * bracketed launch in milliseconds (and its class) in launch order to HOST arrays of
- * `capacity` entries, stores the count in *n_out, and disables timing again.  Events
- * are created inside llm42_profile_enable, never inside a hot call. */
-enum {
-  LLM42_K_PREPARE = 0, LLM42_K_EMBED, LLM42_K_RMSNORM, LLM42_K_QKV, LLM42_K_ATTENTION, LLM42_K_O_PROJ,
-  LLM42_K_GATE_UP, LLM42_K_DOWN, LLM42_K_LM_HEAD, LLM42_K_ARGMAX, LLM42_K_COMMIT, LLM42_K_COUNT
-};
-llm42_status llm42_profile_enable(int32_t kind, int32_t max_launches);
-
-llm42_status llm42_profile_collect(float* ms_out, int32_t* kinds_out, int32_t capacity, int32_t* n_out);
-
-/* Measurement aid for the cost of determinism (not part of the protocol; process-wide, not thread
- * safe).  With on != 0 the next calls drop the two places where the fixed reduction schedule costs
- * time and let the batch decide instead, as an ordinary engine would: with more than 16 rows the two
- * residual projections are not split along k (one accumulator per element instead of p0 + p1), and
- * an attention workgroup that owns a whole 2048-key super accumulates straight through it instead of
- * closing a partial every 256 keys.  Results then stay within rounding of the scheduled ones but are
- * no longer bitwise independent of the batch.  bench.py times one pass each way; nothing else sets it. */
-void llm42_measure_unconstrained(int32_t on);
 
 /* Description of the last error on this thread (host string, never NULL). */
 const char* llm42_last_error(void);

@@ -25,7 +25,7 @@ LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
            "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
-           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_unconstrained", "llm42_decode_step", "llm42_verify_window_sampled",
+           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_verify_window_batch_chosen", "llm42_decode_step", "llm42_verify_window_sampled",
            "llm42_decode_step_sampled", "llm42_prefill", "llm42_prefill_workspace_bytes")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
                   "argmax", "commit")
@@ -106,8 +106,8 @@ def load_library(path: Optional[str] = None):
     lib.llm42_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32,
                                           ctypes.POINTER(i32)]
     lib.llm42_profile_collect.restype = i32
-    lib.llm42_measure_unconstrained.argtypes = [i32]
-    lib.llm42_measure_unconstrained.restype = None
+    lib.llm42_measure_verify_window_batch_chosen.argtypes = lib.llm42_verify_window.argtypes
+    lib.llm42_measure_verify_window_batch_chosen.restype = i32
     lib.llm42_last_error.argtypes = []
     lib.llm42_last_error.restype = ctypes.c_char_p
     lib.llm42_schedule_info.argtypes = []
@@ -195,8 +195,9 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
                         n_valid: Optional[torch.Tensor], max_context: int, out_tokens: torch.Tensor,
                         workspace: torch.Tensor, seq_status: Optional[torch.Tensor] = None,
                         out_logits: Optional[torch.Tensor] = None, dump_seq_ids: Optional[torch.Tensor] = None,
-                        stream=None, sampling: Optional[Sampling] = None) -> None:
-    """sampling given: llm42_verify_window_sampled."""
+                        stream=None, sampling: Optional[Sampling] = None, batch_chosen: bool = False) -> None:
+    """sampling given: llm42_verify_window_sampled.  batch_chosen (measurement only):
+    llm42_measure_verify_window_batch_chosen, the same pass off the fixed schedule."""
     num_seqs = seq_lens.numel()
     if candidates.shape != (num_seqs, window) or out_tokens.shape != (num_seqs, window):
         raise ValueError("candidates / out_tokens must be [num_seqs, window]")
@@ -208,7 +209,11 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
             _ptr(n_valid, torch.int32), num_seqs, max_context, _ptr(out_tokens, torch.int32),
             _ptr(seq_status, torch.int32), _ptr(out_logits, torch.float32), _ptr(dump_seq_ids, torch.int32), n_dump,
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream))
-    if sampling is None:
+    if batch_chosen:
+        if sampling is not None:
+            raise ValueError("the measurement entry has no sampled form")
+        _check(load_library().llm42_measure_verify_window_batch_chosen(*args))
+    elif sampling is None:
         _check(load_library().llm42_verify_window(*args))
     else:
         _check(load_library().llm42_verify_window_sampled(*args, ctypes.byref(sampling)))
@@ -267,11 +272,6 @@ def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_
 
 def llm42_schedule_info() -> str:
     return load_library().llm42_schedule_info().decode()
-
-
-def llm42_measure_unconstrained(on: bool) -> None:
-    """Measurement only: lift (or restore) the fixed reduction schedule, see llm42.h."""
-    load_library().llm42_measure_unconstrained(1 if on else 0)
 
 
 def llm42_profile_enable(kind, max_launches: int) -> None:

@@ -75,19 +75,9 @@ llm42_status check_config(const llm42_config& c) {
   return LLM42_OK;
 }
 
-// Carve the workspace.  Called with base == nullptr to size it.
-Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context, char* base, bool batch_chosen = false) {
+// How the attention work of a call is split (work distribution only; the bits do not depend on it).
+void attention_mode(const llm42_model* m, int num_seqs, int max_context, Workspace& ws) {
   const llm42_config& c = m->cfg;
-  Workspace ws;
-  memset(&ws, 0, sizeof ws);
-  ws.num_cus = m->num_cus;
-  ws.batch_chosen = batch_chosen;
-  ws.m_rows = num_seqs * window;
-  // (384 padded rows would be three token tiles of 128: too few for the 128 x 128 tile to fill the device, and the
-  // 64 x 128 tile then needs a second round of workgroups - 512 padded rows run faster than 384)
-  ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : ws.m_rows <= 64 ? 64
-             : ws.m_rows <= 256 ? pad_to(ws.m_rows, 128) : ws.m_rows <= 512 ? 512 : pad_to(ws.m_rows, 256);
-  ws.r_pad = pad_to(m->group * window, 16);
   // attention work split: per chunk while the grid would otherwise be small, per super beyond that
   const int col_blocks = ws.r_pad / 16, cb_groups = (col_blocks + (col_blocks >= 8 ? 8 : 4) - 1) / (col_blocks >= 8 ? 8 : 4);
   // One workgroup per 2048-key super (chunks folded in registers) once that gives enough workgroups - measured at
@@ -105,6 +95,23 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.attn_direct = supers == 1 && pairs >= 128;
   ws.attn_super = ws.attn_direct || pairs * supers >= 192;
   ws.attn_units = attention_units(ws.attn_super, max_context);
+}
+
+// Carve the workspace.  Called with base == nullptr to size it.
+Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context, char* base, bool batch_chosen = false,
+                size_t min_part_rows = 0) {
+  const llm42_config& c = m->cfg;
+  Workspace ws;
+  memset(&ws, 0, sizeof ws);
+  ws.num_cus = m->num_cus;
+  ws.batch_chosen = batch_chosen;
+  ws.m_rows = num_seqs * window;
+  // (384 padded rows would be three token tiles of 128: too few for the 128 x 128 tile to fill the device, and the
+  // 64 x 128 tile then needs a second round of workgroups - 512 padded rows run faster than 384)
+  ws.m_pad = ws.m_rows <= 16 ? 16 : ws.m_rows <= 32 ? 32 : ws.m_rows <= 64 ? 64
+             : ws.m_rows <= 256 ? pad_to(ws.m_rows, 128) : ws.m_rows <= 512 ? 512 : pad_to(ws.m_rows, 256);
+  ws.r_pad = pad_to(m->group * window, 16);
+  attention_mode(m, num_seqs, max_context, ws);
   size_t off = 0;
   auto take = [&](size_t bytes) {
     char* p = base ? base + off : nullptr;
@@ -123,15 +130,33 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.q = (uint16_t*)take(2ull * num_seqs * c.n_kv_heads * ws.r_pad * c.head_dim);
   ws.attn = (uint16_t*)take(2ull * ws.m_pad * m->d_attn);
   ws.hidden = (uint16_t*)take(2ull * ws.m_pad * m->ffn_k);
-  const size_t part_rows = (size_t)num_seqs * c.n_kv_heads * ws.attn_units * ws.r_pad;
+  // (min_part_rows: llm42_workspace_bytes sizes the partials for every call of up to max_seqs sequences - a call of
+  // fewer sequences may run per chunk where the largest runs per super, with 8 x the slots per sequence)
+  const size_t part_rows = std::max((size_t)num_seqs * c.n_kv_heads * ws.attn_units * ws.r_pad, min_part_rows);
   ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
   ws.part_ml = (float*)take(8ull * part_rows);
-  ws.attn_items = (int4*)take(sizeof(int4) * (size_t)num_seqs * ws.attn_units);
+  ws.attn_items = (int4*)take(sizeof(int4) * std::max((size_t)num_seqs * ws.attn_units, min_part_rows / ((size_t)c.n_kv_heads * ws.r_pad)));
   ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (2 + c.n_layers));
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
   ws.split_part = (float*)take(ws.m_pad > 64 ? 2 * 4ull * ws.m_pad * c.d_model : 0);
   ws.bytes = off;
   return ws;
+}
+
+// Bytes that serve every call of 1 .. max_seqs sequences: everything but the attention partials grows with the
+// number of sequences; the partials depend on the work split as well (a few sequences run per 256-key chunk where many
+// run per 2048-key super), so their slots are counted for every n.
+size_t sized_for_up_to(const llm42_model* m, int max_seqs, int window, int max_context) {
+  Workspace w;
+  memset(&w, 0, sizeof w);
+  w.num_cus = m->num_cus;
+  w.r_pad = pad_to(m->group * window, 16);
+  size_t part_rows = 0;
+  for (int n = 1; n <= max_seqs; ++n) {
+    attention_mode(m, n, max_context, w);
+    part_rows = std::max(part_rows, (size_t)n * m->cfg.n_kv_heads * w.attn_units * w.r_pad);
+  }
+  return carve(m, max_seqs, window, max_context, nullptr, false, part_rows).bytes;
 }
 
 // One pass of the verifier over num_seqs x window rows; arguments already checked.
@@ -185,10 +210,6 @@ PrefillExtra carve_prefill(size_t verifier_bytes, int num_seqs, int window, char
   return x;
 }
 
-// Set by llm42_measure_unconstrained only (a process-wide measurement switch): verifier passes then run off the
-// fixed schedule.  The fast path does not go through it: llm42_decode_step passes its mode down as an argument.
-int g_measure_unconstrained = 0;
-
 // llm42_verify_window_sampled and llm42_decode_step_sampled behind their argument names; batch_chosen: see Workspace.
 llm42_status verify_impl(const char* who, const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
                          const int32_t* candidates, int32_t window, const int32_t* n_valid, int32_t num_seqs,
@@ -225,8 +246,6 @@ extern "C" {
 
 const char* llm42_last_error(void) { return g_err; }
 
-void llm42_measure_unconstrained(int32_t on) { g_measure_unconstrained = on ? 1 : 0; }
-
 const char* llm42_schedule_info(void) {
   return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=2 (halves, p0+p1) for the two residual projections, 1 elsewhere; "
          "attention: step=64 keys, chunk=256, super=2048, left folds; rmsnorm: 16x4 partial sums per row";
@@ -255,6 +274,7 @@ llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w,
       return fail(LLM42_EHIP, "model_create: cannot query the device");
     }
     m->num_cus = cus;
+    m->device = dev;
   }
   m->group = c.n_q_heads / c.n_kv_heads;
   m->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -356,7 +376,7 @@ llm42_status llm42_workspace_bytes(const llm42_model* m, int32_t max_seqs, int32
     return fail(LLM42_EINVAL, "workspace_bytes: max_seqs/window/max_context out of range");
   if ((int64_t)max_seqs * window > LLM42_MAX_ROWS)
     return fail(LLM42_EINVAL, "workspace_bytes: more than %d rows", LLM42_MAX_ROWS);
-  *out_bytes = carve(m, max_seqs, window, max_context, nullptr).bytes;
+  *out_bytes = sized_for_up_to(m, max_seqs, window, max_context);
   return LLM42_OK;
 }
 
@@ -378,7 +398,18 @@ llm42_status llm42_verify_window_sampled(const llm42_model* m, const llm42_kv_ca
                                          const llm42_sampling* sampling) {
   return verify_impl("verify_window", m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context, out_tokens,
                      seq_status, out_logits, dump_seq_ids, n_dump, workspace, workspace_bytes, hip_stream, sampling,
-                     g_measure_unconstrained != 0);
+                     false);
+}
+
+llm42_status llm42_measure_verify_window_batch_chosen(const llm42_model* m, const llm42_kv_cache* kv,
+                                                      const int32_t* seq_lens, const int32_t* candidates,
+                                                      int32_t window, const int32_t* n_valid, int32_t num_seqs,
+                                                      int32_t max_context, int32_t* out_tokens, int32_t* seq_status,
+                                                      float* out_logits, const int32_t* dump_seq_ids, int32_t n_dump,
+                                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return verify_impl("measure_verify_window_batch_chosen", m, kv, seq_lens, candidates, window, n_valid, num_seqs,
+                     max_context, out_tokens, seq_status, out_logits, dump_seq_ids, n_dump, workspace, workspace_bytes,
+                     hip_stream, nullptr, true);
 }
 
 llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,

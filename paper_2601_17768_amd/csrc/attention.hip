@@ -78,7 +78,7 @@ __device__ __forceinline__ void tile_to_lds(uint32_t dst, const uint4* src) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :
                  : "v"(src + i * 64), "s"(dst + i * 1024)
-                 : "memory");
+                 : "memory", "m0");
 }
 // At most N of the fetches this wave has issued are still on their way (they complete in order;
 // the barrier that follows covers the other waves').

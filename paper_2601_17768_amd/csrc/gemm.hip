@@ -473,7 +473,7 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
 // ones, which un-pipelines the operand reads.  The compiler therefore does not count these loads;
 // lds_fetch_wait() is the only wait that covers them.  Nothing else in these kernels uses M0.
 __device__ __forceinline__ void lds_fetch_1k(const void* base, uint32_t voff, uint32_t dst) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(dst) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(dst) : "memory", "m0");
 }
 // acc += a * b with the accumulator pinned to the same four accumulation registers before and after.
 // (Left to the compiler, some instantiations of the tiled kernel compute into a temporary and copy

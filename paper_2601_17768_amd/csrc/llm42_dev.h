@@ -20,6 +20,7 @@
 #include <stdint.h>
 
 #include "../../include/llm42.h"
+#include "../../include/llm42_measure.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -68,7 +69,8 @@ __device__ inline f32x4 mfma16(const bf16x8 a, const bf16x8 b, const f32x4 c) {
 // ---------------------------------------------------------------------------
 struct llm42_model {
   llm42_config cfg;
-  int num_cus;      // compute units of the device the model lives on
+  int device;       // HIP device the model lives on
+  int num_cus;      // compute units of that device
   int group;        // q heads per kv head
   int n_qkv;        // (n_q_heads + 2 n_kv_heads) * head_dim
   int d_attn;       // n_q_heads * head_dim

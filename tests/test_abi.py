@@ -10,13 +10,17 @@ import pytest
 from helpers import ROOT
 from paper_2601_17768_amd import binding as B
 
-HEADER = os.path.join(ROOT, "include", "llm42.h")
+INCLUDE = os.path.join(ROOT, "include")
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(llm42_[a-z_0-9]+)\s*\(", text)))
+    """Every function any header under include/ declares."""
+    names = set()
+    for header in sorted(os.listdir(INCLUDE)):
+        if header.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(INCLUDE, header)).read(), flags=re.S)
+            names.update(re.findall(r"\b(llm42_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_expected_entry_points():

@@ -87,8 +87,9 @@ def test_contexts_around_step_and_chunk_boundaries(tiny):
 
 
 def test_lifting_the_schedule_changes_rounding_only(tiny):
-    """llm42_measure_unconstrained (bench only) lets the batch choose the split of the residual
-    projections: the logits move by rounding, nothing else, and the switch goes back cleanly."""
+    """llm42_measure_verify_window_batch_chosen (bench only) lets the batch choose the split of the residual
+    projections: the logits move by rounding, nothing else; the mode belongs to that one call, so the
+    verifier's own calls before and after it give the same bits."""
     from paper_2601_17768_amd import binding as B
     shape, w, sess = tiny
     rng = wl.rng_for(104, 1)
@@ -101,14 +102,13 @@ def test_lifting_the_schedule_changes_rounding_only(tiny):
     cand = torch.as_tensor(wl.random_tokens(rng, 3 * window, shape.vocab).reshape(3, window).astype(np.int32), device=DEV)
     dump = torch.arange(3, dtype=torch.int32, device=DEV)
     sl = torch.as_tensor(lens, device=DEV)
+    max_context = bt.shape[1] * 16
     _, _, fixed = sess.verify(kv, bt, sl, cand, dump_seq_ids=dump)
     fixed = fixed.clone()
-    B.llm42_measure_unconstrained(True)
-    try:
-        _, _, free = sess.verify(kv, bt, sl, cand, dump_seq_ids=dump)
-        free = free.clone()
-    finally:
-        B.llm42_measure_unconstrained(False)
+    free = torch.zeros_like(fixed)
+    out = torch.empty((3, window), dtype=torch.int32, device=DEV)
+    B.llm42_verify_window(sess.model, kv, num_blocks, bt, sl, cand, window, None, max_context, out,
+                          sess.workspace(3, window, max_context), None, free, dump, batch_chosen=True)
     _, _, again = sess.verify(kv, bt, sl, cand, dump_seq_ids=dump)
     torch.cuda.synchronize()
     assert torch.equal(again, fixed)
