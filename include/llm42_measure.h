@@ -43,6 +43,22 @@ llm42_status llm42_measure_verify_window_batch_chosen(
     int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids, int32_t n_dump,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* How a call of this shape distributes its attention work (the distribution never changes a bit
+ * of the result; tests use this to know which kernels a case exercised).  Writes five values to
+ * the HOST array `out`:
+ *   out[0]  keys per work item: 256 (one workgroup per chunk, all folds in the merge pass) or
+ *           2048 (one per super, chunks folded in registers);
+ *   out[1]  1 if every context fits one 2048-key unit and the attention kernel writes the
+ *           output itself (no merge pass);
+ *   out[2]  1 if the call may take whole sequences as work items - the device decides from the
+ *           lengths whether they deal out evenly enough;
+ *   out[3]  byte offset, in the call's workspace, of the int32 that the device sets to 1 when
+ *           it did take whole sequences (valid after the call has run);
+ *   out[4]  1 if the 8-wave streaming kernel runs (8 or more blocks of 16 query rows per
+ *           sequence and kv head), 0 for the 4-wave kernel. */
+llm42_status llm42_measure_attention_plan(const llm42_model* model, int32_t num_seqs, int32_t window,
+                                          int32_t max_context, int64_t* out);
+
 #ifdef __cplusplus
 }
 #endif

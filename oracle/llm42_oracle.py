@@ -37,7 +37,10 @@ else:
 units).  The residual stream and the logits are never rounded: the device keeps
 them in fp32.  Rounding the residual stream to bf16 as well was tried and
 rejected: two correct evaluations that differ only in summation order then
-drift apart by more than the logit tolerance after 32 layers.  With `round_points` false the whole forward is the
+drift apart by more than the logit tolerance after 32 layers.  (That choice was
+made together with the first device kernel, which keeps the residual stream in
+fp32: here the checker's contract followed the device's, the wider of the two
+options; the paper fixes neither.)  With `round_points` false the whole forward is the
 textbook real-number definition evaluated in `acc_dtype`; that mode is what the
 pins against an independent library implementation and a brute-force
 implementation use.
@@ -202,12 +205,17 @@ def sample_tokens(logits: torch.Tensor, temperature: float, seed: int, request_i
 # --------------------------------------------------------------------------
 def forward_window(cfg: OracleConfig, weights: dict, kv: OracleKV, seq_len: int,
                    tokens: Sequence[int], *, round_points: bool = True,
-                   acc_dtype: torch.dtype = torch.float64) -> torch.Tensor:
+                   acc_dtype: torch.dtype = torch.float64, round_p: bool = False) -> torch.Tensor:
     """Replay `tokens` (n inputs) of ONE sequence whose first `seq_len` cache
     entries are consistent.  Input i sits at absolute position seq_len + i.
     Writes K and V of every input into cache slots seq_len .. seq_len+n-1 (always,
     whatever was there before [§4.2 "Making KV cache consistent"]) and returns the
-    logits [n, vocab] in acc_dtype.  Row i attends to slots 0 .. seq_len+i."""
+    logits [n, vocab] in acc_dtype.  Row i attends to slots 0 .. seq_len+i.
+
+    round_p (off in the definition; used only to measure what one more rounding
+    point costs): the unnormalised softmax weights exp(s - max) are rounded to bf16
+    before they multiply V, while the denominator sums the unrounded weights - the
+    form a bf16 matrix unit needs for the second product of attention."""
     n = len(tokens)
     L = int(seq_len)
     assert n >= 1 and L >= 0 and L + n <= kv.capacity
@@ -240,8 +248,11 @@ def forward_window(cfg: OracleConfig, weights: dict, kv: OracleKV, seq_len: int,
             s = (q[:, h, :] @ keys[:, g, :].T) / math.sqrt(hd)      # [n, L+n]
             s = torch.where(causal, s, torch.full_like(s, -math.inf))
             p = torch.exp(s - s.max(dim=-1, keepdim=True).values)
-            p = p / p.sum(dim=-1, keepdim=True)
-            attn[:, h, :] = p @ vals[:, g, :]
+            if round_p:
+                attn[:, h, :] = (bf16_round(p) @ vals[:, g, :]) / p.sum(dim=-1, keepdim=True)
+            else:
+                p = p / p.sum(dim=-1, keepdim=True)
+                attn[:, h, :] = p @ vals[:, g, :]
         attn = _maybe_round(attn.reshape(n, H * hd), round_points)
         r = r + attn @ lw["wo"].to(f).T
 
@@ -280,7 +291,7 @@ def commit_rollback(inputs: Sequence[int], outputs: Sequence[int], n_valid: int
 def verify_window(cfg: OracleConfig, weights: dict, caches: List[OracleKV],
                   seq_lens: Sequence[int], candidates: Sequence[Sequence[int]],
                   n_valid: Optional[Sequence[int]] = None, *, round_points: bool = True,
-                  acc_dtype: torch.dtype = torch.float64
+                  acc_dtype: torch.dtype = torch.float64, round_p: bool = False
                   ) -> Tuple[List[List[int]], List[torch.Tensor]]:
     """Verifier pass over a group of sequences [§4.3]: every sequence is replayed
     on its own (token positions of different sequences share no data [§3, O3]).
@@ -291,7 +302,7 @@ def verify_window(cfg: OracleConfig, weights: dict, caches: List[OracleKV],
     for s, cand in enumerate(candidates):
         n = len(cand) if n_valid is None else int(n_valid[s])
         logits = forward_window(cfg, weights, caches[s], int(seq_lens[s]), list(cand[:n]),
-                                round_points=round_points, acc_dtype=acc_dtype)
+                                round_points=round_points, acc_dtype=acc_dtype, round_p=round_p)
         out_logits.append(logits)
         out_tokens.append([int(t) for t in greedy_argmax(logits)])
     return out_tokens, out_logits

@@ -25,7 +25,7 @@ LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
            "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
-           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_verify_window_batch_chosen", "llm42_decode_step", "llm42_verify_window_sampled",
+           "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_verify_window_batch_chosen", "llm42_measure_attention_plan", "llm42_decode_step", "llm42_verify_window_sampled",
            "llm42_decode_step_sampled", "llm42_prefill", "llm42_prefill_workspace_bytes")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
                   "argmax", "commit")
@@ -108,6 +108,8 @@ def load_library(path: Optional[str] = None):
     lib.llm42_profile_collect.restype = i32
     lib.llm42_measure_verify_window_batch_chosen.argtypes = lib.llm42_verify_window.argtypes
     lib.llm42_measure_verify_window_batch_chosen.restype = i32
+    lib.llm42_measure_attention_plan.argtypes = [vp, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.llm42_measure_attention_plan.restype = i32
     lib.llm42_last_error.argtypes = []
     lib.llm42_last_error.restype = ctypes.c_char_p
     lib.llm42_schedule_info.argtypes = []
@@ -272,6 +274,14 @@ def llm42_commit_rollback(candidates: torch.Tensor, out_tokens: torch.Tensor, n_
 
 def llm42_schedule_info() -> str:
     return load_library().llm42_schedule_info().decode()
+
+
+def llm42_measure_attention_plan(model: int, num_seqs: int, window: int, max_context: int) -> Dict:
+    """How a call of this shape distributes its attention work (see llm42_measure.h)."""
+    out = (ctypes.c_int64 * 5)()
+    _check(load_library().llm42_measure_attention_plan(model, num_seqs, window, max_context, out))
+    return {"item_keys": out[0], "direct": bool(out[1]), "may_take_sequences": bool(out[2]),
+            "sequences_flag_offset": out[3], "streaming": bool(out[4])}
 
 
 def llm42_profile_enable(kind, max_launches: int) -> None:

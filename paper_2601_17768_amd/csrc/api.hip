@@ -136,6 +136,7 @@ Workspace carve(const llm42_model* m, int num_seqs, int window, int max_context,
   ws.part_acc = (float*)take(4ull * part_rows * c.head_dim);
   ws.part_ml = (float*)take(8ull * part_rows);
   ws.attn_items = (int4*)take(sizeof(int4) * std::max((size_t)num_seqs * ws.attn_units, min_part_rows / ((size_t)c.n_kv_heads * ws.r_pad)));
+  ws.attn_ctrl_offset = off;
   ws.attn_ctrl = (int32_t*)take(sizeof(int32_t) * (2 + c.n_layers));
   ws.amax = (float2*)take(8ull * ws.m_pad * (c.vocab / 16));
   ws.split_part = (float*)take(ws.m_pad > 64 ? 2 * 4ull * ws.m_pad * c.d_model : 0);
@@ -410,6 +411,21 @@ llm42_status llm42_measure_verify_window_batch_chosen(const llm42_model* m, cons
   return verify_impl("measure_verify_window_batch_chosen", m, kv, seq_lens, candidates, window, n_valid, num_seqs,
                      max_context, out_tokens, seq_status, out_logits, dump_seq_ids, n_dump, workspace, workspace_bytes,
                      hip_stream, nullptr, true);
+}
+
+llm42_status llm42_measure_attention_plan(const llm42_model* m, int32_t num_seqs, int32_t window, int32_t max_context,
+                                          int64_t* out) {
+  if (!m || !out) return fail(LLM42_EINVAL, "measure_attention_plan: null argument");
+  if (num_seqs < 1 || window < 1 || window > LLM42_MAX_WINDOW || max_context < 1 ||
+      (int64_t)num_seqs * window > LLM42_MAX_ROWS)
+    return fail(LLM42_EINVAL, "measure_attention_plan: num_seqs/window/max_context out of range");
+  const Workspace ws = carve(m, num_seqs, window, max_context, nullptr);
+  out[0] = ws.attn_super ? 2048 : 256;
+  out[1] = ws.attn_direct ? 1 : 0;
+  out[2] = ws.attn_seq ? 1 : 0;
+  out[3] = (int64_t)(ws.attn_ctrl_offset + sizeof(int32_t) * (1 + m->cfg.n_layers));
+  out[4] = ws.r_pad / 16 >= 8 ? 1 : 0;
+  return LLM42_OK;
 }
 
 llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,

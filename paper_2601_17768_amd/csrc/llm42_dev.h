@@ -108,6 +108,7 @@ struct Workspace {
   int4* attn_items;     // (sequence, unit, length, rows) of every unit that holds keys, built once per call
   int32_t* attn_ctrl;   // [0] number of items, [1 + layer] work queue counter of that layer's attention launch,
                         // [1 + n_layers] 1 if the items are whole sequences
+  size_t attn_ctrl_offset;   // byte offset of attn_ctrl in the workspace
   float* split_part;   // fp32 partials of a split GEMM on the large-batch path, [2][m_pad][d_model]
   float2* amax;   // [m_pad][vocab/16] (value, index bits)
   size_t bytes;

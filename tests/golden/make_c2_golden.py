@@ -11,11 +11,12 @@ K/V cache values of the window, all from the float64 checker.
 
 Also stored ("self_noise"): how far the checker moves when only its accumulation
 precision changes (float32 instead of float64, prompt replayed in four windows
-instead of one) on the very same inputs.  Every bf16 rounding point of the model
+instead of one) on the very same inputs, and how far when the softmax weights
+are rounded to bf16 as well.  Every bf16 rounding point of the model
 turns a last-bit difference in summation order into a one-ulp difference, so two
 correct evaluations with bf16 matrix operands decorrelate; these figures are the
 measured size of that effect at this depth and are what the GPU test scales its
-tolerance by.  `--self-noise-only` recomputes just that part (about 4 minutes).
+tolerance by.  `--self-noise-only` recomputes just that part (about 12 minutes).
 """
 import json
 import os
@@ -43,18 +44,31 @@ def c2_inputs():
 
 
 def self_noise(gold, cfg, w, prompt, cols):
-    """The checker against itself: float32 accumulation, prompt in four windows."""
-    kv = orc.OracleKV(cfg, PROMPT_LEN + WINDOW)
-    for a in range(0, PROMPT_LEN, 128):
-        orc.forward_window(cfg, w, kv, a, prompt[a:a + 128], acc_dtype=torch.float32)
-    lg = orc.forward_window(cfg, w, kv, PROMPT_LEN, gold["candidates"], acc_dtype=torch.float32).double()
+    """The checker against itself on the stored inputs: what moves when a correct evaluation accumulates in
+    float32 instead of float64 (prompt replayed in windows of 128 instead of one), and what moves when, in
+    addition, the softmax weights are rounded to bf16 before they multiply V (`round_p`, the one rounding point
+    a bf16 matrix unit adds to the definition), for two different cuts of the prompt into windows - the spread
+    between those two is the error bar of the figure."""
     ref = torch.tensor(gold["logits_at_columns"], dtype=torch.float64)
-    d = (lg[:, torch.as_tensor(cols)] - ref).abs()
-    toks = [int(t) for t in orc.greedy_argmax(lg)]
-    return {"_what": "float32-accumulation checker minus float64 checker at the stored columns",
-            "rms": float((d * d).mean().sqrt()), "max": float(d.max()),
-            "fraction_within_2e-2": float((d <= 2e-2).double().mean()),
-            "rows_with_a_different_argmax": int(sum(a != b for a, b in zip(toks, gold["out_tokens"])))}
+
+    def one(round_p, cut):
+        kv = orc.OracleKV(cfg, PROMPT_LEN + WINDOW)
+        for a in range(0, PROMPT_LEN, cut):
+            orc.forward_window(cfg, w, kv, a, prompt[a:a + cut], acc_dtype=torch.float32, round_p=round_p)
+        lg = orc.forward_window(cfg, w, kv, PROMPT_LEN, gold["candidates"], acc_dtype=torch.float32,
+                                round_p=round_p).double()
+        d = (lg[:, torch.as_tensor(cols)] - ref).abs()
+        toks = [int(t) for t in orc.greedy_argmax(lg)]
+        return {"rms": float((d * d).mean().sqrt()), "max": float(d.max()),
+                "fraction_within_2e-2": float((d <= 2e-2).double().mean()),
+                "rows_with_a_different_argmax": int(sum(a != b for a, b in zip(toks, gold["out_tokens"])))}
+
+    plain = one(False, 128)
+    rp = [one(True, 128), one(True, 64)]
+    return {"_what": "float32-accumulation checker minus float64 checker at the stored columns; 'with_p_rounding': the "
+                     "same with the softmax weights rounded to bf16 before P V (prompt cut into windows of 128 and of 64)",
+            **plain, "with_p_rounding": rp,
+            "model_rms": sum(x["rms"] for x in rp) / len(rp), "model_max": sum(x["max"] for x in rp) / len(rp)}
 
 
 def main():

@@ -28,6 +28,9 @@ def assert_logits_close(gpu: torch.Tensor, ref: torch.Tensor, what: str = ""):
     return err, rms
 
 
+NOISE_FACTOR = 1.5   # GPU error allowed relative to the checker-only noise model (measured: 0.9 .. 1.2)
+
+
 def assert_logits_within_noise(gpu: torch.Tensor, ref: torch.Tensor, noise_rms: float, noise_max: float,
                                what: str = ""):
     """Logit tolerance at the 8B model's widths (logit std 1.3, |logit| up to 7).
@@ -36,15 +39,18 @@ def assert_logits_within_noise(gpu: torch.Tensor, ref: torch.Tensor, noise_rms: 
     for ANY two correct evaluations with bf16 matrix operands, the checker against itself
     included: each of the model's bf16 rounding points turns a last-bit difference in
     summation order into a one-ulp (0.4 %) difference, and after a few layers the two
-    evaluations are decorrelated at that level.  Measured with the checker alone (float32
-    vs float64 accumulation, same inputs): 2 layers rms 5.8e-3 / max 3.3e-2; all 32
-    layers at context 512 rms 2.6e-2 / max 9.4e-2, with different arg-max on some rows.
-    The tolerance is therefore scaled by that measured self-noise (noise_rms, noise_max,
-    computed by the checker on the same inputs): rms error <= 2 noise_rms, max error
-    <= 2 noise_max, and the error must look like noise - no bias (|mean| <= noise_rms/4),
-    no scale error (|slope against the reference| <= 5e-3), correlation >= 0.998.  A
-    structural mistake (wrong index, sign, scale, missing term) gives errors of the order
-    of the logit std, 30 to 100 times the noise.  Returns (max abs error, rms error)."""
+    evaluations are decorrelated at that level.  Measured with the checker alone at these widths
+    (float32 against float64 accumulation, same inputs): one layer rms 3.9e-3 / max 2.2e-2, two
+    layers 6.2e-3 / 3.5e-2, all 32 layers at context 512 rms 2.6e-2 / max 9.4e-2.  A bf16 matrix
+    unit adds one rounding point to the definition - the softmax weights are rounded before they
+    multiply V - and that alone moves the checker by rms 6.8e-3 / max 3.7e-2 at one layer.
+    The tolerance is therefore the checker's own noise on the same inputs with both effects in
+    (noise_rms, noise_max: float32 accumulation and rounded softmax weights against the float64
+    definition): rms error <= 1.5 noise_rms, max error <= 1.5 noise_max, and the error must
+    look like noise - no bias (|mean| <= noise_rms/4), no scale error (|slope against the
+    reference| <= 5e-3), correlation >= 0.998.  A structural mistake (wrong index, sign, scale,
+    missing term) gives errors of the order of the logit std, 30 to 100 times the noise.
+    Returns (max abs error, rms error)."""
     g = gpu.detach().cpu().double()
     r = ref.double()
     assert torch.isfinite(g).all(), f"{what}: non-finite GPU logits"
@@ -54,14 +60,26 @@ def assert_logits_within_noise(gpu: torch.Tensor, ref: torch.Tensor, noise_rms: 
     slope = float((e * rc).sum() / (rc * rc).sum())
     corr = float(torch.corrcoef(torch.stack([g.flatten(), r.flatten()]))[0, 1])
     frac = float((e.abs() <= ABS_TOL).double().mean())
-    print(f"{what}: max {err:.3e} (noise {noise_max:.3e}) rms {rms:.3e} (noise {noise_rms:.3e}) within-2e-2 {frac:.4f} "
-          f"mean {float(e.mean()):.2e} slope {slope:.2e} corr {corr:.6f} std {float(r.std()):.3f}", flush=True)
-    assert rms <= 2 * noise_rms, f"{what}: rms error {rms:.3e} > 2 x {noise_rms:.3e}"
-    assert err <= 2 * noise_max, f"{what}: max error {err:.3e} > 2 x {noise_max:.3e}"
+    print(f"{what}: max {err:.3e} = {err / noise_max:.2f} x noise, rms {rms:.3e} = {rms / noise_rms:.2f} x noise, "
+          f"within-2e-2 {frac:.4f} mean {float(e.mean()):.2e} slope {slope:.2e} corr {corr:.6f} std {float(r.std()):.3f} "
+          f"max/scale {err / float(r.abs().max()):.2e}", flush=True)
+    assert rms <= NOISE_FACTOR * noise_rms, f"{what}: rms error {rms:.3e} > {NOISE_FACTOR} x {noise_rms:.3e}"
+    assert err <= NOISE_FACTOR * noise_max, f"{what}: max error {err:.3e} > {NOISE_FACTOR} x {noise_max:.3e}"
     assert abs(float(e.mean())) <= noise_rms / 4, f"{what}: biased error {float(e.mean()):.3e}"
     assert abs(slope) <= 5e-3, f"{what}: error scales with the logit, slope {slope:.3e}"
     assert corr >= 0.998, f"{what}: correlation {corr:.6f}"
     return err, rms
+
+
+def checker_noise(cfg, weights, prefix_k, prefix_v, L, tokens, ref_logits):
+    """The checker's own noise on one window: float32 accumulation and bf16-rounded softmax weights against the
+    float64 definition (ref_logits), on the same cached prefix and inputs.  Returns the |difference| tensor."""
+    n = len(tokens)
+    kv = orc.OracleKV(cfg, L + n)
+    kv.k[:, :L] = prefix_k[:, :L]
+    kv.v[:, :L] = prefix_v[:, :L]
+    lg = orc.forward_window(cfg, weights, kv, L, tokens, acc_dtype=torch.float32, round_p=True).double()
+    return (lg - ref_logits.double()).abs()
 
 
 def assert_tokens_match_where_decidable(gpu_tokens, gpu_logits, ref_tokens, ref_logits, what=""):

@@ -114,3 +114,32 @@ def test_lifting_the_schedule_changes_rounding_only(tiny):
     assert torch.equal(again, fixed)
     assert not torch.equal(free, fixed)          # a different reduction order does show in the last bits
     assert float((free - fixed).abs().max()) < 2e-2   # the logit tolerance; measured 4e-3 (bf16 rounding points amplify last-bit differences)
+
+
+def test_one_workspace_serves_every_smaller_call(tiny):
+    """llm42_workspace_bytes(max_seqs, ...) is enough for every call of 1 .. max_seqs sequences, although a call
+    of fewer sequences may split its attention work finer (per 256-key chunk instead of per 2048-key super) and
+    then needs more partial slots per sequence."""
+    from paper_2601_17768_amd import binding as B
+    shape, w, sess = tiny
+    window, max_seqs, max_context = 16, 110, 512
+    rng = wl.rng_for(105, 1)
+    ws = torch.empty(B.llm42_workspace_bytes(sess.model, max_seqs, window, max_context), dtype=torch.uint8, device=DEV)
+    modes = set()
+    lens = wl.uniform_lengths(rng, max_seqs, 1, max_context - window)
+    table, num_blocks = wl.make_block_table(rng, lens + window, 16, max_blocks_per_seq=max_context // 16, spare_blocks=2)
+    kv = sess.kv_cache(num_blocks)
+    kv.normal_(generator=torch.Generator(device=DEV).manual_seed(6))
+    bt = torch.as_tensor(table, device=DEV)
+    cand = torch.as_tensor(wl.random_tokens(rng, max_seqs * window, shape.vocab).reshape(max_seqs, window).astype(np.int32), device=DEV)
+    sl = torch.as_tensor(lens, device=DEV)
+    for n in range(1, max_seqs + 1):
+        assert B.llm42_workspace_bytes(sess.model, n, window, max_context) <= ws.numel()
+        plan = B.llm42_measure_attention_plan(sess.model, n, window, max_context)
+        modes.add((plan["item_keys"], plan["direct"]))
+        out = torch.empty((n, window), dtype=torch.int32, device=DEV)
+        B.llm42_verify_window(sess.model, kv, num_blocks, bt[:n].contiguous(), sl[:n].contiguous(), cand[:n].contiguous(),
+                              window, None, max_context, out, ws)
+    torch.cuda.synchronize()
+    assert int(out.min()) >= 0
+    assert modes == {(256, False), (2048, True)}      # both work splits were crossed

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from helpers import orc, wl
-from gpu_helpers import Scenario, VerifierSession, assert_logits_within_noise, oracle_kv_to_gpu, gpu_kv_tokens, assert_tokens_match_where_decidable, ABS_TOL
+from gpu_helpers import Scenario, VerifierSession, assert_logits_within_noise, checker_noise, REL_TOL, oracle_kv_to_gpu, gpu_kv_tokens, assert_tokens_match_where_decidable, ABS_TOL
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -20,8 +20,11 @@ def as_dtype(w, dtype):
 
 
 @pytest.mark.timeout(600)
-def test_mid_shape_against_checker():
-    shape = wl.LLAMA_8B.replace(n_layers=2, vocab=32064)
+@pytest.mark.parametrize("n_layers", [1, 2])
+def test_mid_shape_against_checker(n_layers):
+    """One layer: nothing amplifies a rounding difference yet, and still the checker's own noise (printed) reaches
+    the benchmark spec's 2e-2; the relative bound (1e-2 of the largest logit) holds and is asserted literally."""
+    shape = wl.LLAMA_8B.replace(n_layers=n_layers, vocab=32064)
     w = wl.make_weights(shape, seed=43)
     sess = VerifierSession(shape, w, max_position=1024, device=DEV)
     rng = wl.rng_for(43, 1)
@@ -41,21 +44,16 @@ def test_mid_shape_against_checker():
     torch.cuda.synchronize()
     assert status.tolist() == [0, 0, 0]
     o_tokens, o_logits = sc.oracle_verify()
-    # the checker's own sensitivity to accumulation order on these inputs: float32 instead of float64
+    # the checker's own noise on these inputs: float32 accumulation and rounded softmax weights against the definition
     w32 = as_dtype(w, torch.float32)
-    noise = []
-    for s in range(3):
-        L = int(sc.lens[s])
-        kv32 = orc.OracleKV(sc.cfg, L + window)
-        kv32.k[:, :L] = sc.okv[s].k[:, :L]
-        kv32.v[:, :L] = sc.okv[s].v[:, :L]
-        lg32 = orc.forward_window(sc.cfg, w32, kv32, L, sc.candidates[s], acc_dtype=torch.float32).double()
-        noise.append((lg32 - o_logits[s]).abs())
-    noise = torch.cat(noise)
+    noise = torch.cat([checker_noise(sc.cfg, w32, sc.okv[s].k, sc.okv[s].v, int(sc.lens[s]), sc.candidates[s], o_logits[s])
+                       for s in range(3)])
     noise_rms, noise_max = float((noise * noise).mean().sqrt()), float(noise.max())
+    print(f"{n_layers} layer(s): checker noise rms {noise_rms:.3e} max {noise_max:.3e}")
     exempt = 0
     for s in range(3):
-        err, rms = assert_logits_within_noise(logits[s], o_logits[s], noise_rms, noise_max, f"mid shape seq {s}")
+        err, rms = assert_logits_within_noise(logits[s], o_logits[s], noise_rms, noise_max, f"{n_layers}-layer shape seq {s}")
+        assert err <= REL_TOL * float(o_logits[s].abs().max())           # spec relative bound, literally
         margin = orc.top2_margin(o_logits[s])
         seq_exempt = assert_tokens_match_where_decidable(out[s].cpu(), logits[s], o_tokens[s], o_logits[s], f"seq {s}")
         exempt += seq_exempt

@@ -126,7 +126,7 @@ def _bf16_np(x):
     return b.astype(np.uint32).view(np.float32).astype(np.float64)
 
 
-def _brute_force_logits(shape, w, ids, rnd):
+def _brute_force_logits(shape, w, ids, rnd, round_p=False):
     """Scalar-loop forward without any cache: every row recomputes attention over
     the whole token list.  Written separately from the checker on purpose."""
     R = _bf16_np if rnd else (lambda a: np.asarray(a, dtype=np.float64))
@@ -173,7 +173,10 @@ def _brute_force_logits(shape, w, ids, rnd):
                 e = [math.exp(s - mx) for s in sc]
                 z = sum(e)
                 for t in range(i + 1):
-                    att[i, h * hd:(h + 1) * hd] += e[t] / z * v[t, g * hd:(g + 1) * hd]
+                    if round_p:     # rounded weight in the numerator, unrounded weights in the denominator
+                        att[i, h * hd:(h + 1) * hd] += float(_bf16_np(e[t])) * v[t, g * hd:(g + 1) * hd] / z
+                    else:
+                        att[i, h * hd:(h + 1) * hd] += e[t] / z * v[t, g * hd:(g + 1) * hd]
         x = x + R(att) @ f(lw["wo"]).T
         y = R(norm(x, f(lw["ffn_norm"])))
         ga, up = y @ f(lw["w_gate"]).T, y @ f(lw["w_up"]).T
@@ -199,6 +202,31 @@ def test_forward_matches_scalar_brute_force(rnd):
     if rnd:
         # such flips are rare: the bulk must agree to fp64 accuracy
         assert np.median(np.abs(got - ref)) < 1e-9
+
+
+def test_softmax_weight_rounding_option_matches_scalar_brute_force():
+    """round_p: exp(s - max) rounded to bf16 where it multiplies V, the denominator from the unrounded weights.
+    With every other rounding point off the two implementations must agree to fp64 accuracy, and the option
+    must move the result by about one bf16 rounding of the attention output, no more."""
+    shape = wl.ModelShape(n_layers=2, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ffn=48,
+                          vocab=64, rope_theta=100.0)
+    w = randomize_gains(wl.make_weights(shape, seed=5, std=0.3))
+    ids = wl.random_tokens(wl.rng_for(6), 11, shape.vocab)
+    cfg = oracle_cfg(shape)
+    kv = orc.OracleKV(cfg, 16)
+    orc.forward_window(cfg, w, kv, 0, ids[:6], round_points=False, round_p=True)
+    got = orc.forward_window(cfg, w, kv, 6, ids[6:], round_points=False, round_p=True).numpy()
+    ref = _brute_force_logits(shape, w, ids, False, round_p=True)[6:]
+    plain = _brute_force_logits(shape, w, ids, False)[6:]
+    scale = max(1.0, np.abs(ref).max())
+    assert np.abs(got - ref).max() < 1e-11 * scale
+    moved = np.abs(ref - plain).max() / scale
+    assert 1e-6 < moved < 2.0 ** -7, moved
+    # a softmax over one key has weight exactly 1: nothing to round, the option changes nothing
+    kv1 = orc.OracleKV(cfg, 4)
+    a = orc.forward_window(cfg, w, kv1, 0, ids[:1], round_p=True)
+    b = orc.forward_window(cfg, w, orc.OracleKV(cfg, 4), 0, ids[:1], round_p=False)
+    assert torch.equal(a, b)
 
 
 # ------------------------------------------------------- structure ----------
