@@ -161,6 +161,23 @@ llm42_status llm42_verify_window(
     size_t                workspace_bytes,
     void*                 hip_stream);   /* hipStream_t; NULL = default stream           */
 
+/* llm42_verify_window for callers that cannot allocate or pass device scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, effects and
+ * results (bit for bit) as llm42_verify_window, without `workspace`: the pass runs in a scratch
+ * area of LLM42_STATIC_SCRATCH_BYTES that is part of the library's device image (each GPU on which
+ * a model was created holds one copy until the process ends; its device address is looked up once
+ * per device in llm42_model_create).  The call allocates nothing and frees nothing.
+ * LLM42_EWORKSPACE if the call needs more than the area holds (what it needs is
+ * llm42_workspace_bytes of its own num_seqs, window and max_context); LLM42_EINVAL if the model's
+ * device is not the current one.  All calls on one GPU share the one area, which keeps the
+ * previous call's contents (every pass rewrites what it reads, nothing has to start at zero):
+ * calls that overlap in time on the same GPU - other streams, other threads - race; order them. */
+#define LLM42_STATIC_SCRATCH_BYTES (64u << 20)
+llm42_status llm42_verify_window_static(
+    const llm42_model* model, const llm42_kv_cache* kv_cache, const int32_t* seq_lens, const int32_t* candidates,
+    int32_t window, const int32_t* n_valid, int32_t num_seqs, int32_t max_context, int32_t* out_tokens,
+    int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids, int32_t n_dump, void* hip_stream);
+
 /* Accept rule [Section 4.2].  For sequence s with n = n_valid[s] inputs:
  * m = number of leading candidates with candidates[s][i+1] == out_tokens[s][i],
  * i < n-1.  committed_counts[s] = m+1 (>= 1: forward progress); committed_tokens

@@ -21,10 +21,11 @@ LLM42_OK, LLM42_EINVAL, LLM42_ESHAPE, LLM42_EWORKSPACE, LLM42_ECAPACITY, LLM42_E
 LLM42_KV_BLOCK = 16
 LLM42_MAX_WINDOW = 512
 LLM42_MAX_ROWS = 65536
+LLM42_STATIC_SCRATCH_BYTES = 64 << 20
 LLM42_SEQ_OK, LLM42_SEQ_BAD_LENGTH, LLM42_SEQ_BAD_BLOCK, LLM42_SEQ_BAD_TOKEN = 0, 1, 2, 4
 
 EXPORTS = ("llm42_model_create", "llm42_model_destroy", "llm42_kv_bytes", "llm42_workspace_bytes",
-           "llm42_verify_window", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
+           "llm42_verify_window", "llm42_verify_window_static", "llm42_commit_rollback", "llm42_last_error", "llm42_schedule_info",
            "llm42_profile_enable", "llm42_profile_collect", "llm42_measure_verify_window_batch_chosen", "llm42_measure_attention_plan", "llm42_decode_step", "llm42_verify_window_sampled",
            "llm42_decode_step_sampled", "llm42_prefill", "llm42_prefill_workspace_bytes")
 KERNEL_CLASSES = ("prepare", "embed", "rmsnorm", "qkv", "attention", "o_proj", "gate_up", "down", "lm_head",
@@ -88,6 +89,8 @@ def load_library(path: Optional[str] = None):
     lib.llm42_verify_window.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, i32,
                                         vp, ctypes.c_size_t, vp]
     lib.llm42_verify_window.restype = i32
+    lib.llm42_verify_window_static.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, i32, vp]
+    lib.llm42_verify_window_static.restype = i32
     lib.llm42_verify_window_sampled.argtypes = lib.llm42_verify_window.argtypes + [ctypes.POINTER(Sampling)]
     lib.llm42_verify_window_sampled.restype = i32
     lib.llm42_decode_step.argtypes = [vp, ctypes.POINTER(KVCache), vp, vp, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
@@ -219,6 +222,26 @@ def llm42_verify_window(model: int, kv_base: torch.Tensor, num_blocks: int, bloc
         _check(load_library().llm42_verify_window(*args))
     else:
         _check(load_library().llm42_verify_window_sampled(*args, ctypes.byref(sampling)))
+
+
+def llm42_verify_window_static(model: int, kv_base: torch.Tensor, num_blocks: int, block_table: torch.Tensor,
+                               seq_lens: torch.Tensor, candidates: torch.Tensor, window: int,
+                               n_valid: Optional[torch.Tensor], max_context: int, out_tokens: torch.Tensor,
+                               seq_status: Optional[torch.Tensor] = None, out_logits: Optional[torch.Tensor] = None,
+                               dump_seq_ids: Optional[torch.Tensor] = None, stream=None) -> None:
+    """llm42_verify_window in the library's built-in scratch area (no workspace argument)."""
+    num_seqs = seq_lens.numel()
+    if candidates.shape != (num_seqs, window) or out_tokens.shape != (num_seqs, window):
+        raise ValueError("candidates / out_tokens must be [num_seqs, window]")
+    n_dump = 0 if dump_seq_ids is None else dump_seq_ids.numel()
+    if n_dump and (out_logits is None or out_logits.shape[0] != n_dump or out_logits.shape[1] != window):
+        raise ValueError("out_logits must be [n_dump, window, vocab]")
+    kv = _kv_view(model, kv_base, num_blocks, block_table, num_seqs)
+    _check(load_library().llm42_verify_window_static(
+        model, ctypes.byref(kv), _ptr(seq_lens, torch.int32), _ptr(candidates, torch.int32), window,
+        _ptr(n_valid, torch.int32), num_seqs, max_context, _ptr(out_tokens, torch.int32),
+        _ptr(seq_status, torch.int32), _ptr(out_logits, torch.float32), _ptr(dump_seq_ids, torch.int32), n_dump,
+        _stream_handle(stream)))
 
 
 def llm42_decode_step(model: int, kv_base: torch.Tensor, num_blocks: int, block_table: torch.Tensor,

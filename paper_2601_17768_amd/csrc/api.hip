@@ -6,11 +6,21 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "llm42_dev.h"
 
+// Scratch area of llm42_verify_window_static: one copy per GPU that loads the library, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the device address it yields (one per
+// device) is what kernels, copies and fills are given.
+static __device__ __align__(256) unsigned char scratch[LLM42_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, set by llm42_model_create
+std::mutex g_scratch_mutex;
 
 thread_local char g_err[512] = "";
 
@@ -276,6 +286,20 @@ llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w,
     }
     m->num_cus = cus;
     m->device = dev;
+    // the address of this device's copy of the built-in scratch area (looked up once per device, here, with the
+    // device current; llm42_verify_window_static only reads the table)
+    if (dev < kMaxDevices) {
+      std::lock_guard<std::mutex> lock(g_scratch_mutex);
+      if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t se = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (se != hipSuccess || !ptr) {
+          delete m;
+          return fail(LLM42_EHIP, "model_create: hipGetSymbolAddress(scratch): %s", hipGetErrorString(se));
+        }
+        g_scratch_ptr[dev] = ptr;
+      }
+    }
   }
   m->group = c.n_q_heads / c.n_kv_heads;
   m->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -426,6 +450,29 @@ llm42_status llm42_measure_attention_plan(const llm42_model* m, int32_t num_seqs
   out[3] = (int64_t)(ws.attn_ctrl_offset + sizeof(int32_t) * (1 + m->cfg.n_layers));
   out[4] = ws.r_pad / 16 >= 8 ? 1 : 0;
   return LLM42_OK;
+}
+
+llm42_status llm42_verify_window_static(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
+                                        const int32_t* candidates, int32_t window, const int32_t* n_valid,
+                                        int32_t num_seqs, int32_t max_context, int32_t* out_tokens,
+                                        int32_t* seq_status, float* out_logits, const int32_t* dump_seq_ids,
+                                        int32_t n_dump, void* hip_stream) {
+  if (!m) return fail(LLM42_EINVAL, "verify_window_static: null argument");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != m->device)
+    return fail(LLM42_EINVAL, "verify_window_static: the model lives on device %d, current device is %d", m->device, dev);
+  void* ptr = dev >= 0 && dev < kMaxDevices ? g_scratch_ptr[dev] : nullptr;
+  if (!ptr) return fail(LLM42_EHIP, "verify_window_static: no scratch address for device %d", dev);
+  if (window >= 1 && window <= LLM42_MAX_WINDOW && num_seqs >= 1 && (int64_t)num_seqs * window <= LLM42_MAX_ROWS &&
+      max_context >= 1) {
+    const size_t need = carve(m, num_seqs, window, max_context, nullptr).bytes;
+    if (need > LLM42_STATIC_SCRATCH_BYTES)
+      return fail(LLM42_EWORKSPACE, "verify_window_static: this call needs %zu bytes of scratch, the built-in area holds %zu",
+                  need, (size_t)LLM42_STATIC_SCRATCH_BYTES);
+  }
+  return verify_impl("verify_window_static", m, kv, seq_lens, candidates, window, n_valid, num_seqs, max_context,
+                     out_tokens, seq_status, out_logits, dump_seq_ids, n_dump, ptr, LLM42_STATIC_SCRATCH_BYTES, hip_stream,
+                     nullptr, false);
 }
 
 llm42_status llm42_decode_step(const llm42_model* m, const llm42_kv_cache* kv, const int32_t* seq_lens,
