@@ -257,9 +257,9 @@ def test_stale_and_poisoned_slots_are_never_read(env):
     assert part[3][:5].tolist() == clean[3][:5].tolist() and part[3][5:].tolist() == [-1, -1, -1]
 
 
-def test_long_context_across_the_attention_superchunk_boundary(env):
-    """Context > 1024 keys: several attention partials are merged; checked against the
-    checker and for invariance to batch company and window split."""
+def test_long_context_over_several_attention_chunks(env):
+    """Context of 1035 keys: five 256-key chunk partials are merged; checked against the
+    checker and for invariance to batch company.  (Contexts past a 2048-key super: test_gpu_attention_modes.py.)"""
     shape, w, sess = env
     cfg = oracle_cfg(shape)
     rng = wl.rng_for(42, 8)
