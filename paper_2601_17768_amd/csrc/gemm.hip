@@ -453,9 +453,10 @@ __global__ __launch_bounds__(512) void gemm_xshare_kernel(const bf16x8* __restri
   }
 }
 
-// Large-batch kernel (more than 64 tokens): MFMA-bound, LDS-tiled.  A workgroup of 4 waves (2 x 2)
-// owns a tile of 32*WBN features x 32*WBM tokens; each wave owns WBN x WBM MFMA blocks (WBN*WBM*4
-// accumulator registers).  Per stage of one k-tile the four waves move the tile's 2*(WBN+WBM) operand
+// Large-batch kernel (more than 64 tokens): MFMA-bound, LDS-tiled.  A workgroup of 2*WN waves (WN along
+// the features x 2 along the tokens; WN = 2 unless stated) owns a tile of 16*WN*WBN features x 32*WBM
+// tokens; each wave owns WBN x WBM MFMA blocks (WBN*WBM*4
+// accumulator registers).  Per stage of one k-tile the waves move the tile's WN*WBN + 2*WBM operand
 // tiles (1 KiB each, already in MFMA operand order) from global memory straight into a ring of NST
 // stages in LDS; every wave reads its WBN weight operands and WBM activation operands per k-tile
 // with conflict-free 16-byte LDS reads.  WGS workgroups share a CU: one wave per SIMD cannot keep
@@ -491,15 +492,17 @@ __device__ __forceinline__ void lds_fetch_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int WBN, int WBM, int NST, int WGS, bool ADD_PARTIAL, class Epi>
-__global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
+template <int WBN, int WBM, int NST, int WGS, bool ADD_PARTIAL, class Epi, int WN = 2>
+__global__ __launch_bounds__(128 * WN, WGS) void gemm_tiled_kernel(const bf16x8* __restrict__ w, const bf16x8* __restrict__ x,
                                                          int n_blocks, int k_tiles, int k_begin, int k_count,
                                                          const float* __restrict__ partial, int n, int tiles_n,
                                                          int tiles_m, int sm_tiles, int group_tiles, int planes, Epi epi) {
-  constexpr int TBN = 2 * WBN, TBM = 2 * WBM;   // 16-row blocks per tile side (features, tokens)
+  constexpr int TBN = WN * WBN, TBM = 2 * WBM;  // 16-row blocks per tile side (features, tokens)
   constexpr int ST = TBN + TBM;                 // operand tiles per stage of one k-tile (weights then activations)
-  constexpr int PW = ST / 4;                    // operand tiles each wave fetches per stage
-  static_assert(ST % 4 == 0, "a stage's tiles are dealt evenly to the four waves");
+  constexpr int NWV = 2 * WN;                   // waves per workgroup: WN along the features x 2 along the tokens
+  constexpr int PW = (ST + NWV - 1) / NWV;      // operand tiles each wave fetches per stage (where ST is no multiple of
+                                                // the wave count the last waves fetch the stage's last tile again: the same
+                                                // bytes to the same place, which keeps every wave's fetch count the same)
   // NST = ring of stages in LDS
   __shared__ bf16x8 lds[NST][ST * 64];
   // wave index as a scalar, so that everything derived from it (operand addresses) stays in SGPRs
@@ -536,7 +539,7 @@ __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __re
   const bf16x8* src[PW];
 #pragma unroll
   for (int i = 0; i < PW; ++i) {
-    const int q = wave * PW + i;                       // 0 .. ST-1
+    const int q = min(wave * PW + i, ST - 1);          // 0 .. ST-1
     const bool is_w = q < TBN;
     const int blk = is_w ? q : q - TBN;
     const int gb = is_w ? min(n0 + blk, n_blocks - 1) : m0 + blk;   // feature blocks past the matrix re-read the last one
@@ -547,7 +550,7 @@ __global__ __launch_bounds__(256, WGS) void gemm_tiled_kernel(const bf16x8* __re
     const uint32_t voff = (uint32_t)min(s, k_count - 1) * 1024u + (uint32_t)lane * 16u;
 #pragma unroll
     for (int i = 0; i < PW; ++i)
-      lds_fetch_1k(src[i], voff, lds_addr + (uint32_t)(((s % NST) * ST + wave * PW + i) * 1024));
+      lds_fetch_1k(src[i], voff, lds_addr + (uint32_t)(((s % NST) * ST + min(wave * PW + i, ST - 1)) * 1024));
   };
   f32x4 acc[WBN][WBM];
 #pragma unroll
@@ -643,10 +646,11 @@ __global__ __launch_bounds__(256) void split_combine_kernel(const float* __restr
 // side_by_side (split GEMMs only): both k-halves in one launch of twice the workgroups plus a small
 // combining pass, instead of two launches one after the other - for launches that do not fill the
 // device by themselves.  The arithmetic per output element is the same either way.
-template <int WBN, int WBM, int NST, int WGS, int SPLIT, class Epi>
+template <int WBN, int WBM, int NST, int WGS, int SPLIT, class Epi, int WN = 2>
 void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles, int n, const Workspace& ws,
                   const Epi& epi, hipStream_t st, bool side_by_side = false) {
-  const int tiles_n = (n_blocks + 2 * WBN - 1) / (2 * WBN), tiles_m = ws.m_pad / (32 * WBM);
+  const int tiles_n = (n_blocks + WN * WBN - 1) / (WN * WBN), tiles_m = ws.m_pad / (32 * WBM);
+  constexpr unsigned threads = 128 * WN;
   const int planes = SPLIT == 2 && side_by_side ? 2 : 1;
   // Super-tiles of g = sn x sm tiles (see the kernel), dealt round-robin to the 8 XCDs.  sm: as square as the tiles
   // allow (a 128 x 256 tile counts double on the token side), but the widest that leaves at most 15 % of the token
@@ -654,7 +658,7 @@ void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles,
   // with free LDS before they can leave (1280 rows took as long as 2048 that way; a column of width 1 on the other
   // hand makes every XCD fetch 32 weight tiles per k-step, which cost 4 % at 1792 rows).  g: the largest of 32, 16, 8, 4 that leaves
   // the busiest XCD within 3 % of the least workgroup slots any of them gives it (few super-tiles deal out unevenly).
-  const int sm_max = WBM > WBN ? 4 : 8;
+  const int sm_max = 2 * WBM > WN * WBN ? 4 : 8;
   int g = 4, sm = 1, sn = 4, supers = 0;
   long long least = -1;
   for (int pass = 0; pass < 2; ++pass)
@@ -677,23 +681,23 @@ void launch_tiled(const bf16x8* wp, const bf16x8* xp, int n_blocks, int k_tiles,
     }
   const unsigned grid = 8u * (unsigned)g * (unsigned)((supers + 7) / 8);
   if (SPLIT == 1) {
-    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles, nullptr,
-                                                                            n, tiles_n, tiles_m, sm, g, 1, epi);
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, Epi, WN><<<grid, threads, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, k_tiles,
+                                                                                    nullptr, n, tiles_n, tiles_m, sm, g, 1, epi);
     return;
   }
   const int h = split_point(k_tiles);
   const size_t plane = (size_t)ws.m_pad * n;
   StorePartialEpi pe{ws.split_part, n, plane};
   if (side_by_side) {
-    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi><<<grid, 256, 0, st>>>(
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi, WN><<<grid, threads, 0, st>>>(
         wp, xp, n_blocks, k_tiles, 0, h, nullptr, n, tiles_n, tiles_m, sm, g, 2, pe);
     split_combine_kernel<Epi><<<dim3((n_blocks + 3) / 4, ws.m_pad / 16), 256, 0, st>>>(ws.split_part, ws.split_part + plane,
                                                                                       n_blocks, n, epi);
   } else {
-    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi><<<grid, 256, 0, st>>>(
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, false, StorePartialEpi, WN><<<grid, threads, 0, st>>>(
         wp, xp, n_blocks, k_tiles, h, k_tiles - h, nullptr, n, tiles_n, tiles_m, sm, g, 1, pe);
-    gemm_tiled_kernel<WBN, WBM, NST, WGS, true, Epi><<<grid, 256, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part,
-                                                                           n, tiles_n, tiles_m, sm, g, 1, epi);
+    gemm_tiled_kernel<WBN, WBM, NST, WGS, true, Epi, WN><<<grid, threads, 0, st>>>(wp, xp, n_blocks, k_tiles, 0, h, ws.split_part,
+                                                                                   n, tiles_n, tiles_m, sm, g, 1, epi);
   }
 }
 
@@ -746,6 +750,16 @@ void launch_gemm(const uint16_t* w, const uint16_t* x, int n_blocks, int k_padde
   const int p = side_by_side ? 2 : 1;
   constexpr bool kLogits = std::is_same<Epi, LogitsEpi>::value, kQkv = std::is_same<Epi, QkvEpi>::value;
   const bool big = !kLogits && (kQkv ? t256 >= 2 * cus : t256 * p * 5 >= 4 * cus);
+  if constexpr (!std::is_same<Epi, SwigluEpi>::value) {
+    // 768 and 1024 rows (and 1280 of the QKV projection): too few 128 x 256 tiles for two workgroups per CU, and one
+    // workgroup of four waves per CU keeps neither the MFMA pipe nor the fetch path busy.  The same tile with EIGHT
+    // waves (32 x 128 per wave, one workgroup per CU, six stages in flight) measured 3 - 13 % faster on these
+    // launches (not on gate/up, whose 128 x 128 tiles already fill the device twice over).
+    if (m_pad == 768 || m_pad == 1024 || (kQkv && m_pad == 1280)) {
+      launch_tiled<2, 8, 6, 1, SPLIT, Epi, 4>(wp, xp, n_blocks, k_tiles, n, ws, epi, st, side_by_side);
+      return;
+    }
+  }
   if constexpr (kQkv) {
     // A 192 x 128 tile where it puts the whole QKV projection into one round of workgroups (two per CU) and the
     // 128 x 128 tile would need a second one: 2048 rows of the 8B shape are 512 such tiles (3.67 -> 3.24 ms per pass).

@@ -51,7 +51,7 @@ def test_batch_size_position_and_repeat_invariance(env):
     target_window = wl.random_tokens(rng, window, shape.vocab)
     ref = _batch(sess, shape, [target_prompt], [target_window], window, 0, seed=1)
     checked = 0
-    for others in (1, 2, 7, 12, 24, 32, 63):      # 16 .. 512 rows: every GEMM kernel variant is crossed
+    for others in (1, 2, 7, 12, 24, 32, 63, 90, 127):      # 16 .. 1024 rows: every GEMM kernel variant is crossed
         comp_lens = wl.uniform_lengths(rng, others, 8, 200)
         comp = [wl.random_tokens(rng, int(n), shape.vocab) for n in comp_lens]
         comp_win = [wl.random_tokens(rng, window, shape.vocab) for _ in range(others)]
@@ -63,7 +63,7 @@ def test_batch_size_position_and_repeat_invariance(env):
                 for a, b in zip(ref, got):
                     assert torch.equal(a, b), (others, slot, rep)
                 checked += 1
-    assert checked == 7 * 3 * 2 - 2     # others=1 has two distinct slots only
+    assert checked == 9 * 3 * 2 - 2     # others=1 has two distinct slots only
 
 
 def test_split_of_positions_into_windows_does_not_matter(env):
