@@ -258,8 +258,9 @@ extern "C" {
 const char* llm42_last_error(void) { return g_err; }
 
 const char* llm42_schedule_info(void) {
-  return "llm42-gfx950 0.1; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=2 (halves, p0+p1) for the two residual projections, 1 elsewhere; "
-         "attention: step=64 keys, chunk=256, super=2048, left folds; rmsnorm: 16x4 partial sums per row";
+  return "llm42-gfx950 0.2; gemm: v_mfma_f32_16x16x32_bf16, k ascending, split_k=2 (halves, p0+p1) for the two residual projections, 1 elsewhere; "
+         "attention: step=64 keys, chunk=256, super=2048, left folds, a partial's reference exponent moves when a step's maximum exceeds it by more than 8 (log2); "
+         "rmsnorm: 16x4 partial sums per row";
 }
 
 llm42_status llm42_model_create(const llm42_config* cfg, const llm42_weights* w, llm42_model** out) {

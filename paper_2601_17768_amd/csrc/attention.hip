@@ -37,6 +37,7 @@
 namespace {
 
 constexpr int STEP = 64, CHUNK = 256, SUPER_KEYS = 2048;
+constexpr float kLazy = 8.0f;   // log2 units, see softmax_step
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -138,7 +139,7 @@ __device__ __forceinline__ void store_output(uint16_t* __restrict__ out, int d_a
 template <int HD, int CB, bool MASKED>
 __device__ __forceinline__ void softmax_step(const uint4* lk, const uint16_t* lv, int k0, int k_hi, int lane,
                                              float scale_log2, const bf16x8 (&qf)[CB][HD / 32], const int (&qpos)[CB],
-                                             float (&m)[CB], float (&l)[CB], f32x4 (&acc)[CB][HD / 16]) {
+                                             float (&m)[CB], float (&l)[CB], f32x4 (&acc)[CB][HD / 16], const bool first) {
   constexpr int DK = HD / 32, DB = HD / 16, TV4 = HD * 2;
   const int col = lane & 15, g = lane >> 4;
   constexpr int RV = 4;                                     // V operands in flight
@@ -190,7 +191,11 @@ __device__ __forceinline__ void softmax_step(const uint4* lk, const uint16_t* lv
     mx = fmaxf(fmaxf(mx, sc[cb][3][1]), sc[cb][3][2]);
     mx = rows_max(fmaxf(mx, sc[cb][3][3]));
     // scaling by a positive constant is monotonic: max(scaled) == scaled(max), bit for bit
-    const float m_new = fmaxf(m[cb], mx * scale_log2);
+    const float m_step = mx * scale_log2;
+    // The partial's reference exponent m moves up to this step's maximum only when that exceeds it by more than
+    // kLazy (then p = exp2(score - m) stays at or below 2^kLazy); otherwise it stands and alpha is exactly 1.
+    // (An empty partial has m = -inf: +inf > kLazy takes the step's maximum; -inf - -inf is NaN and keeps -inf.)
+    const float m_new = (m_step - m[cb] > kLazy) ? m_step : m[cb];
     const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m[cb] - m_use);
     float rs = 0.f;
@@ -202,10 +207,15 @@ __device__ __forceinline__ void softmax_step(const uint4* lk, const uint16_t* lv
       rs += ((sc[cb][b][0] + sc[cb][b][1]) + sc[cb][b][2]) + sc[cb][b][3];
     }
     rs = rows_sum(rs);
-    l[cb] = l[cb] * alpha + rs;
-    m[cb] = m_new;
+    // Rescaling by alpha is skipped where it cannot change a bit: in the first step of a partial (l and acc are
+    // zero, and zero times alpha is zero) and where alpha is exactly 1 for every row of the wave.
+    if (!first && __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+      l[cb] *= alpha;
 #pragma unroll
-    for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
+      for (int d = 0; d < DB; ++d) acc[cb][d] *= alpha;
+    }
+    l[cb] += rs;
+    m[cb] = m_new;
     // k-slot e of lane group g is key g*4+e of the first block of a pair (e < 4) or of the
     // second (e >= 4); V uses the same assignment
 #pragma unroll
@@ -372,10 +382,11 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
       const int k0 = k_lo + j * STEP;
       const uint4* sk = &lds_k[j & (NBUF - 1)][0];
       const uint16_t* sv = (const uint16_t*)&lds_v[j & (NBUF - 1)][0];
+      const bool first = SUPER ? (j & 3) == 0 : j == 0;        // the chunk partial is empty
       if (k0 + STEP - 1 <= wmin)                               // wave-uniform
-        softmax_step<HD, CB, false>(sk, sv, k0, k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+        softmax_step<HD, CB, false>(sk, sv, k0, k_hi, lane, scale_log2, qf, qpos, m, l, acc, first);
       else
-        softmax_step<HD, CB, true>(sk, sv, k0, k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+        softmax_step<HD, CB, true>(sk, sv, k0, k_hi, lane, scale_log2, qf, qpos, m, l, acc, first);
     }
     if (SUPER && ((j & 3) == 3 || j + 1 == n_steps)) {
       // a chunk is complete: fold it into the running super partial and start the next one afresh
@@ -583,10 +594,11 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
 #pragma unroll
         for (int d = 0; d < DK; ++d) qf[0][d] = ((const bf16x8*)q_keep)[wave * TV4 + d * 64 + lane];
       }
+      const bool first = SUPER && FOLD ? (j & 3) == 0 : j == 0;   // the chunk partial is empty
       if (k0 + STEP - 1 <= wmin)                               // wave-uniform
-        softmax_step<HD, CB, false>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+        softmax_step<HD, CB, false>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc, first);
       else
-        softmax_step<HD, CB, true>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc);
+        softmax_step<HD, CB, true>(sk, sv, k0, c.k_hi, lane, scale_log2, qf, qpos, m, l, acc, first);
       if (SUPER && FOLD && ((j & 3) == 3 || j + 1 == c.n_steps)) {
         // a chunk is complete: fold it into the running super partial and start the next one afresh
         if ((SEQ ? (j & 31) : j) < 4) {
