@@ -35,12 +35,12 @@ def counter_per_launch(directory: str, counter: str, regex: str):
         rows += list(csv.DictReader(open(path)))
     pick = lambda pat: [float(r["Counter_Value"]) for r in rows
                         if r["Counter_Name"] == counter and re.search(pat, r["Kernel_Name"])]
-    # the calibration kernel is the elementwise launch that moves the most (torch's fills and copies of the same run
-    # match the name too, but none of them reads AND writes 256 MiB)
-    kern, cal = pick(regex), pick("elementwise")
+    # the calibration kernel: bench.py's `torch.add(x, 1.0, out=y)` on 64 Mi floats (torch's fills and copies of the
+    # same run are elementwise kernels too, but not this functor)
+    kern, cal = pick(regex), pick(r"elementwise.*_add<float>")
     if not kern or not cal:
         raise SystemExit(f"{directory}: no {counter} rows for /{regex}/ ({len(kern)}) or the calibration kernel ({len(cal)})")
-    return sum(kern) / len(kern), max(cal), len(kern)
+    return sum(kern) / len(kern), sum(cal) / len(cal), len(kern)
 
 
 def main():
