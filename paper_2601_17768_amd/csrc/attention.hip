@@ -71,15 +71,22 @@ __device__ inline void fold(float& M, float& L, f32x4 (&A)[NV], float m2, float 
 // assembly on purpose: with the compiler's own form of this load every later LDS read waits for
 // all earlier ones, which un-pipelines the operand reads of the steps.  The compiler therefore
 // does not count these loads; fetch_landed() is the only wait that covers them.  Nothing else in
-// this kernel uses M0.
-template <int TL>
+// this kernel uses M0.  STREAM marks the load non-temporal: K and V tiles are read once per (sequence,
+// kv head) and launch, and the hint takes the fetch stream alone (no arithmetic) from 5.1 to 5.7 TB/s.
+template <int TL, bool STREAM = false>
 __device__ __forceinline__ void tile_to_lds(uint32_t dst, const uint4* src) {
 #pragma unroll
   for (int i = 0; i < TL; ++i)
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(src + i * 64), "s"(dst + i * 1024)
-                 : "memory", "m0");
+    if constexpr (STREAM)
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
+                   :
+                   : "v"(src + i * 64), "s"(dst + i * 1024)
+                   : "memory", "m0");
+    else
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                   :
+                   : "v"(src + i * 64), "s"(dst + i * 1024)
+                   : "memory", "m0");
 }
 // At most N of the fetches this wave has issued are still on their way (they complete in order;
 // the barrier that follows covers the other waves').
@@ -347,8 +354,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     const int id = bj < 64 ? __builtin_amdgcn_readlane(ids0, bj & 63) : __builtin_amdgcn_readlane(ids1, bj & 63);
     const uint32_t off = (uint32_t)(((j & (NBUF - 1)) * 4 + blk) * TV4 + part * PIECES * 64) * 16;
     const size_t src = ((size_t)id * n_kv_heads + kvh) * TV4 + part * PIECES * 64 + lane;
-    tile_to_lds<PIECES>(lds_k_addr + off, k_plane + src);
-    tile_to_lds<PIECES>(lds_v_addr + off, v_plane + src);
+    tile_to_lds<PIECES, true>(lds_k_addr + off, k_plane + src);
+    tile_to_lds<PIECES, true>(lds_v_addr + off, v_plane + src);
   };
 
   float m[CB], l[CB];
@@ -527,8 +534,8 @@ __global__ __launch_bounds__(512) void attention_stream_kernel(
     } else {
       const size_t src = ((size_t)f_id * n_kv_heads + f.kvh) * TV4 + part * (TL / 2) * 64 + lane;
       const uint32_t off = (uint32_t)(blk * TV4 + part * (TL / 2) * 64) * 16;
-      tile_to_lds<TL / 2>(slot + off, k_plane + src);
-      tile_to_lds<TL / 2>(slot + (uint32_t)(4 * TV4) * 16 + off, v_plane + src);
+      tile_to_lds<TL / 2, true>(slot + off, k_plane + src);
+      tile_to_lds<TL / 2, true>(slot + (uint32_t)(4 * TV4) * 16 + off, v_plane + src);
     }
     if (f.valid) {
       if (++f_entry > f.n_steps) {
